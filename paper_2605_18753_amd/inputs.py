@@ -1,0 +1,145 @@
+"""Seeded synthetic inputs for the DashAttention forward path.
+
+This module only draws random tensors; it contains none of the method's
+arithmetic.  It serves the tests (which hand the same bits to the CPU oracle
+and to the HIP library) and the benchmark.
+
+Recipe (every workload): Q, K, V are i.i.d. N(0,1) drawn in fp32; every key of
+KV block c of (batch b, kv-head r) gets the same additive offset vector
+o[b,r,c,:] ~ N(0, offset_sigma^2), so block means differ and the entmax
+router becomes sparse; the "needle" variant instead adds +needle_gain * u to
+the keys of a few randomly chosen blocks, u ~ N(0, I_d) shared by all kv-heads
+of a sequence.  Tensors are rounded once (RNE) to the run dtype; those bits are
+the input of both sides.  Q is NOT pre-scaled: the 1/sqrt(d) factor is applied
+once, inside the attention (Eq. 1 of the paper).
+
+Draw order is fixed (Q, K, V, offsets / needles, one batch element at a time)
+so a (workload, seed, device type) triple always yields the same bits.  CPU and
+GPU generators produce different streams; a test that needs both sides to see
+the same data copies the generated tensors, it never regenerates them.
+"""
+from __future__ import annotations
+
+import dataclasses
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    batch: int
+    h_q: int
+    h_kv: int
+    n_q: int            # prefill: == n_kv ; decode: 1
+    n_kv: int
+    head_dim: int
+    block: int
+    alpha: float = 1.5
+    gamma: float = 1.0
+    sigma: float = 1.0
+    causal: bool = True
+    dtype: str = "bf16"          # "bf16" | "fp32"
+    offset_sigma: float = 0.5    # std of the per-block key offset
+    needles: int = 0             # >0: needle recipe instead of offsets
+    needle_gain: float = 2.0
+    seed: int = 0
+
+    def replace(self, **kw) -> "Workload":
+        return dataclasses.replace(self, **kw)
+
+    @property
+    def g_q(self) -> int:
+        return self.h_q // self.h_kv
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+
+
+# The five configurations the build is measured / checked on.
+C1 = Workload("C1_single_head_fp32", 1, 1, 1, 1024, 1024, 64, 64, causal=False,
+              dtype="fp32", offset_sigma=0.5)
+C2 = Workload("C2_causal_gqa_prefill_32k", 1, 32, 8, 32768, 32768, 128, 64,
+              offset_sigma=0.5)
+C3 = Workload("C3_causal_gqa_decode_128k", 16, 32, 8, 1, 131072, 128, 64,
+              offset_sigma=0.7)
+C4 = Workload("C4_long_prefill_128k", 1, 32, 8, 131072, 131072, 128, 128,
+              offset_sigma=0.5)
+C5 = Workload("C5_training_shaped_needles", 4, 16, 16, 8192, 8192, 128, 64,
+              offset_sigma=0.0, needles=4)
+
+NAMED = {w.name.split("_")[0]: w for w in (C1, C2, C3, C4, C5)}
+
+
+def _gen(device, seed: int) -> torch.Generator:
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    return g
+
+
+def _randn(shape, gen, device) -> torch.Tensor:
+    return torch.randn(shape, generator=gen, device=device, dtype=torch.float32)
+
+
+def _add_block_structure(w: Workload, k: torch.Tensor, gen, device) -> None:
+    """In place: add per-block offsets (or needles) to the fp32 keys of one
+    batch element, k: [h_kv, n_kv, d]."""
+    h_kv, n, d = k.shape
+    n_blocks = (n + w.block - 1) // w.block
+    if w.needles > 0:
+        u = _randn((d,), gen, device)
+        # distinct blocks, chosen with the same generator
+        perm = torch.randperm(n_blocks, generator=gen, device=device)
+        for c in perm[: w.needles].tolist():
+            k[:, c * w.block:(c + 1) * w.block, :] += w.needle_gain * u
+    elif w.offset_sigma > 0.0:
+        off = _randn((h_kv, n_blocks, d), gen, device) * w.offset_sigma
+        off = off.repeat_interleave(w.block, dim=1)[:, :n, :]
+        k += off
+
+
+def make_inputs(w: Workload, device="cpu") -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Return (q, k, v) in the run dtype.
+
+    Layout: q [batch, h_q, n_q, d]; k, v [batch, h_kv, n_kv, d]; last dim
+    contiguous.  For a decode workload (n_q == 1) the single query sits at
+    position n_kv - 1 and k, v are the KV cache (which already holds that
+    token).
+    """
+    device = torch.device(device)
+    gen = _gen(device, w.seed)
+    dt = w.torch_dtype
+    q = torch.empty((w.batch, w.h_q, w.n_q, w.head_dim), dtype=dt, device=device)
+    k = torch.empty((w.batch, w.h_kv, w.n_kv, w.head_dim), dtype=dt, device=device)
+    v = torch.empty_like(k)
+    for b in range(w.batch):
+        q[b] = _randn((w.h_q, w.n_q, w.head_dim), gen, device).to(dt)
+        kb = _randn((w.h_kv, w.n_kv, w.head_dim), gen, device)
+        vb = _randn((w.h_kv, w.n_kv, w.head_dim), gen, device)
+        _add_block_structure(w, kb, gen, device)
+        k[b] = kb.to(dt)
+        v[b] = vb.to(dt)
+        del kb, vb
+    return q, k, v
+
+
+def shrink(w: Workload, *, n: Optional[int] = None, batch: Optional[int] = None,
+           h_q: Optional[int] = None, h_kv: Optional[int] = None,
+           name: Optional[str] = None) -> Workload:
+    """A smaller workload with the same recipe (used by parity tests that the
+    oracle must finish in seconds)."""
+    kw = {}
+    if n is not None:
+        kw["n_kv"] = n
+        kw["n_q"] = 1 if w.n_q == 1 else n
+    if batch is not None:
+        kw["batch"] = batch
+    if h_q is not None:
+        kw["h_q"] = h_q
+    if h_kv is not None:
+        kw["h_kv"] = h_kv
+    kw["name"] = name or (w.name + "_small")
+    return w.replace(**kw)
