@@ -1,0 +1,158 @@
+/*
+ * dash_attn.h -- C ABI of the MI355X (gfx950) DashAttention forward library.
+ *
+ * The library implements the forward hot path of DashAttention:
+ *   Stage 0  block-mean key summaries                     (Sec. 3.1, Eq. 3 at a zero
+ *                                                          summary query; Alg. 1)
+ *   Stage 1  entmax chunk routing per query, GQA averaged  (Sec. 3.2, Eq. 4; Alg. 2)
+ *            + the routing bias of the prior               (Sec. 3.4, Proposition 1)
+ *   Stage 2  block-sparse softmax attention over the kept  (Sec. 3.3, Eq. 5-6 in the
+ *            chunks with the bias added to the logits       bias form of Prop. 1; Alg. 3)
+ *   plus a split-KV decode variant of Stage 2 (Sec. 3.5) and a dense reference
+ *   attention (Eq. 1).
+ *
+ * Conventions shared by every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     allocates no device memory, keeps no state between calls, never
+ *     synchronises, and enqueues all work on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream).
+ *   - Tensors are [batch, head, token, head_dim] with head_dim contiguous; the
+ *     other three strides are given in ELEMENTS in dash_params.  Rows must be
+ *     16-byte aligned (base pointers 16-byte aligned, strides multiples of 8
+ *     elements for bf16 / 4 for fp32).
+ *   - Return value: DASH_OK (0) or a negative dash_status.  On a non-zero return
+ *     nothing was enqueued (validation errors) or the outputs are undefined
+ *     (DASH_ELAUNCH).  No exceptions or aborts cross this boundary.
+ *   - Query index t of the n_q queries sits at sequence position
+ *     n_kv - n_q + t.  Prefill passes n_q == n_kv; decode passes n_q == 1 and a
+ *     KV cache that already contains the current token.
+ *   - Causal: the routing candidates of a query are the complete chunks strictly
+ *     before its own chunk (Alg. 2, "c < c_i"); its own chunk is always attended,
+ *     causally masked, with bias 0 (the diagonal branch).  Non-causal: every
+ *     chunk is a candidate, there is no diagonal branch, and n_kv must be a
+ *     multiple of block_size (dense_attn and the size queries accept any n_kv).
+ *   - kbar pointers may be NULL when n_kv < block_size (no complete chunk).
+ */
+#ifndef DASH_ATTN_H_
+#define DASH_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dash_status {
+  DASH_OK = 0,
+  DASH_EINVAL = -1,       /* NULL pointer, non-positive size, h_q % h_kv != 0, alpha <= 1, ...   */
+  DASH_EUNSUPPORTED = -2, /* a combination this build has no kernel for (see dash_params)         */
+  DASH_EWORKSPACE = -3,   /* workspace NULL / misaligned / smaller than dash_attn_workspace_bytes */
+  DASH_ELAUNCH = -4       /* the HIP runtime reported an error at launch                          */
+} dash_status;
+
+enum { DASH_F32 = 0, DASH_BF16 = 1 };
+
+typedef struct dash_params {
+  int32_t batch;       /* >= 1                                                        */
+  int32_t h_q;         /* query heads                                                 */
+  int32_t h_kv;        /* key/value heads; g_q = h_q / h_kv in {1,2,4,8,16}           */
+  int32_t n_q;         /* queries per sequence                                        */
+  int32_t n_kv;        /* keys per sequence, n_kv >= n_q                              */
+  int32_t head_dim;    /* 64 or 128                                                   */
+  int32_t block_size;  /* chunk size B: 64 or 128                                     */
+  int32_t causal;      /* 0 / 1                                                       */
+  int32_t dtype;       /* DASH_F32 or DASH_BF16: element type of q, k, v, o           */
+  float alpha;         /* entmax alpha, > 1                                           */
+  float gamma;         /* Stage-1 temperature (Eq. 4), > 0                            */
+  float sigma;         /* prior strength (Sec. 3.4), > 0; large => pure block mask    */
+  float scale;         /* logit scale; <= 0 selects 1/sqrt(head_dim)                  */
+  int64_t q_stride[3]; /* batch, head, token strides of q, in elements               */
+  int64_t k_stride[3];
+  int64_t v_stride[3];
+  int64_t o_stride[3];
+} dash_params;
+
+/* Number of chunk slots per query in the list outputs below:
+ * ceil(n_kv / block_size) (candidates plus the diagonal chunk). */
+int32_t dash_list_stride(const dash_params* p);
+
+/* Number of 32-bit words per query in the bit-packed chunk mask (Alg. 2's M,
+ * 32 chunks per word, bit c%32 of word c/32): ceil(dash_list_stride / 32). */
+int32_t dash_mask_words(const dash_params* p);
+
+/* Bytes of device scratch the calls below need for these parameters (host
+ * computation only).  The workspace must be 256-byte aligned. */
+int dash_attn_workspace_bytes(const dash_params* p, size_t* out_bytes);
+
+/* Stage 0 (Eq. 3 at zero summary query = uniform mean; Alg. 1).
+ *   k     in  [batch,h_kv,n_kv,d] run dtype, strides k_stride
+ *   kbar  out [batch,h_kv,T_c,d] fp32 contiguous, T_c = floor(n_kv/block_size):
+ *         the mean of each complete chunk, accumulated exactly and rounded once
+ *         to fp32.  This is the persistent chunk-summary cache of Sec. 3.5.
+ *   first_chunk, n_chunks: the chunk range to (re)compute, e.g. only a chunk
+ *         that was just completed during decoding; n_chunks < 0 means all. */
+int dash_kbar_compress(const dash_params* p, const void* k, float* kbar,
+                       int32_t first_chunk, int32_t n_chunks, void* stream);
+
+/* Stage 1 (Eq. 4, GQA averaging, Prop. 1 bias; Alg. 2).
+ *   q     in  [batch,h_q,n_q,d]
+ *   kbar  in  fp32 summaries from dash_kbar_compress
+ * Outputs, each [batch,h_kv,n_q,...] contiguous; any of blk_cnt/blk_idx/tau may
+ * be NULL (not produced); mask and blk_bias may be NULL, in which case they are
+ * kept inside the workspace for dash_stage2_attend:
+ *   mask     uint32 [.., dash_mask_words]   bit c set iff chunk c is attended
+ *            (routed chunks, plus the diagonal chunk when causal)
+ *   blk_cnt  int32  [..]                    number of attended chunks
+ *   blk_idx  int32  [.., dash_list_stride]  their ids, ascending (diagonal last)
+ *   blk_bias fp32   [.., dash_list_stride]  d_{i,c} in the same order (0 for the
+ *            diagonal chunk); entries past blk_cnt are unspecified
+ *   tau      fp32   [batch,h_q,n_q]         entmax threshold of every query head
+ *            in the domain x = gamma (alpha-1) <q,kbar> scale (0 if no candidate) */
+int dash_stage1_route(const dash_params* p, const void* q, const float* kbar,
+                      uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx,
+                      float* blk_bias, float* tau,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Stage 2 (Eq. 6 in the bias form of Prop. 1; Alg. 3): for every query,
+ * softmax over the tokens of its attended chunks of (q.k*scale + d), times v.
+ *   mask, blk_bias: as produced by dash_stage1_route (NULL = read them from the
+ *   same workspace the Stage-1 call used).  o out [batch,h_q,n_q,d]. */
+int dash_stage2_attend(const dash_params* p, const void* q, const void* k,
+                       const void* v, void* o, const uint32_t* mask,
+                       const float* blk_bias,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Whole prefill path: Stage 0 (all chunks) -> Stage 1 -> Stage 2.
+ * kbar is an output (the caller keeps it as the summary cache); the list
+ * outputs are optional as in dash_stage1_route. */
+int dash_attn_prefill(const dash_params* p, const void* q, const void* k,
+                      const void* v, void* o, float* kbar, uint32_t* mask,
+                      int32_t* blk_cnt, int32_t* blk_idx, float* blk_bias,
+                      float* tau, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+/* One decode step (n_q must be 1; always causal): Stage 1 on the cached
+ * summaries, then split-KV Stage 2 and the log-sum-exp merge of the partial
+ * results (Sec. 3.5).  kbar_cache is in/out: if the current token completes a
+ * chunk (n_kv % block_size == 0) that chunk's summary is written first; the
+ * other entries are read only.  List outputs optional as above. */
+int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache,
+                     const void* v_cache, float* kbar_cache, void* o,
+                     uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx,
+                     float* blk_bias, float* tau,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Dense reference attention (Eq. 1), same tensors and layouts, no routing.
+ * The denominator of every speed-up figure.  alpha/gamma/sigma/block_size are
+ * ignored except for validation. */
+int dense_attn(const dash_params* p, const void* q, const void* k, const void* v,
+               void* o, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static, NUL-terminated description of a dash_status. */
+const char* dash_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DASH_ATTN_H_ */

@@ -18,7 +18,8 @@ What each function follows (paper sections / equations / algorithms):
   prior_literal,
   attend_literal         Eq. 5-8 taken literally (w', lambda via KL + sigmoid, g)
   dense_attention        Eq. 1
-  dash_row, dash_rows    the whole path for one (batch, kv-head, query) triple
+  dash_row_at, dash_row,
+  dash_rows              the whole path for one (batch, kv-head, query) triple
 
 Pins (tests/test_oracle_*.py, all CPU): entmax closed forms, simplex
 invariants, alpha=2 == Euclidean projection, alpha->1 == softmax, brute force
@@ -44,7 +45,7 @@ __all__ = [
     "block_mean_summaries", "entmax_threshold_exact", "entmax_threshold_bisect",
     "entmax_threshold", "entmax", "route_token", "prior_bias",
     "attend_bias_form", "prior_literal", "attend_literal", "dense_attention",
-    "DashParams", "RowResult", "dash_row", "dash_rows", "dash_forward_full",
+    "DashParams", "RowResult", "dash_row_at", "dash_row", "dash_rows", "dash_forward_full",
 ]
 
 
@@ -313,23 +314,20 @@ class RowResult:
     o: np.ndarray          # [g_q, d]
 
 
-def dash_row(q, k, v, kbar, prm: DashParams, b: int, r: int, iq: int) -> RowResult:
-    """One (batch b, kv-head r, query index iq) of the forward path.
+def dash_row_at(qh, k, v, kbar, prm: DashParams, pos: int, ident=(0, 0, 0)) -> RowResult:
+    """The forward path for the g_q query heads qh [g_q, d] of one kv-head at
+    sequence position pos, against that head's keys/values k, v [n_kv, d] and
+    summaries kbar [T_c, d].
 
-    q [B,H_q,n_q,d], k, v [B,H_kv,n_kv,d] hold run-dtype values; kbar
-    [B,H_kv,T_c,d] comes from block_mean_summaries.  Query iq sits at position
-    n_kv - n_q + iq (prefill: iq; decode with n_q = 1: the last cached token).
     Causal: candidates are the chunks strictly before the query's own chunk,
     and the diagonal branch is the causal part of that chunk.  Non-causal: all
     chunks are candidates and there is no diagonal branch.
     """
-    n_q, d = q.shape[2], q.shape[3]
-    n_kv = k.shape[2]
-    g_q = q.shape[1] // k.shape[1]
+    qh = np.asarray(qh, dtype=np.float64)
+    g_q, d = qh.shape
+    n_kv = k.shape[0]
     scale = prm.scale if prm.scale is not None else 1.0 / math.sqrt(d)
     blk = prm.block
-    pos = n_kv - n_q + iq
-    qh = np.asarray(q[b, r * g_q:(r + 1) * g_q, iq, :], dtype=np.float64)
     if prm.causal:
         n_cand = pos // blk
         diag = (n_cand * blk, pos + 1)
@@ -338,13 +336,28 @@ def dash_row(q, k, v, kbar, prm: DashParams, b: int, r: int, iq: int) -> RowResu
         n_cand = n_kv // blk
         diag = (0, 0)
     if n_cand > 0:
-        x, tau, _, w = route_token(qh, kbar[b, r, :n_cand], prm.alpha, prm.gamma, scale)
+        x, tau, _, w = route_token(qh, kbar[:n_cand], prm.alpha, prm.gamma, scale)
         routed, bias = prior_bias(w, prm.sigma)
     else:
         x = np.zeros((g_q, 0)); tau = np.zeros(g_q); w = np.zeros(0)
         routed = np.zeros(0, dtype=np.int64); bias = np.zeros(0)
-    o = attend_bias_form(qh, k[b, r], v[b, r], scale, blk, routed, bias, diag[0], diag[1])
-    return RowResult(b, r, iq, pos, n_cand, x, tau, w, routed, bias, diag, o)
+    o = attend_bias_form(qh, k, v, scale, blk, routed, bias, diag[0], diag[1])
+    return RowResult(ident[0], ident[1], ident[2], pos, n_cand, x, tau, w, routed, bias, diag, o)
+
+
+def dash_row(q, k, v, kbar, prm: DashParams, b: int, r: int, iq: int) -> RowResult:
+    """One (batch b, kv-head r, query index iq) of the forward path.
+
+    q [B,H_q,n_q,d], k, v [B,H_kv,n_kv,d] hold run-dtype values; kbar
+    [B,H_kv,T_c,d] comes from block_mean_summaries.  Query iq sits at position
+    n_kv - n_q + iq (prefill: iq; decode with n_q = 1: the last cached token).
+    """
+    n_q = q.shape[2]
+    n_kv = k.shape[2]
+    g_q = q.shape[1] // k.shape[1]
+    pos = n_kv - n_q + iq
+    return dash_row_at(q[b, r * g_q:(r + 1) * g_q, iq, :], k[b, r], v[b, r], kbar[b, r], prm, pos,
+                       (b, r, iq))
 
 
 def dash_rows(q, k, v, prm: DashParams, rows: Iterable[Tuple[int, int, int]],

@@ -1,0 +1,53 @@
+// Host-side internals of the DashAttention library: derived sizes, the layout
+// of the caller-provided workspace, and the launchers each kernel file exports.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/dash_attn.h"
+
+namespace dash {
+
+struct Layout {
+  int g_q;          // query heads per kv head
+  int t_c;          // complete chunks: floor(n_kv / block)  (have a summary)
+  int t_all;        // ceil(n_kv / block) = list stride (candidates + diagonal)
+  int words;        // mask words per query
+  int pos0;         // sequence position of query 0: n_kv - n_q
+  int splits;       // decode: KV splits per (batch, kv head)
+  float scale;      // logit scale
+  float xscale;     // gamma * (alpha-1) * scale: Stage-1 score factor
+  float pexp;       // 1/(alpha-1)
+  bool use_mfma;    // bf16 prefill path (split summaries + MFMA Stage 1/2)
+  // workspace offsets in bytes (256-aligned); 0-sized regions share offsets
+  size_t off_ksplit, off_mask, off_bias, off_scores, off_part, total;
+};
+
+// Validates p and fills L.  Returns a dash_status.  routing = false skips the
+// checks that only the Stage-1 router needs (dense attention, size queries).
+int make_layout(const dash_params* p, Layout* L, bool routing = true);
+
+struct S1Out {
+  uint32_t* mask; int32_t* cnt; int32_t* idx; float* bias; float* tau;
+};
+
+hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const void* k, float* kbar,
+                                int first_chunk, int n_chunks, hipStream_t st);
+hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const void* q,
+                                const float* kbar, float* scores, hipStream_t st);
+// ksplit != NULL: bf16 MFMA scorer (the split of kbar is written to ksplit first);
+// otherwise the scores are read from `scores` (written by launch_s1_scores_f32).
+hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q, const float* kbar,
+                           uint16_t* ksplit, const float* scores, const S1Out& out, hipStream_t st);
+hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, const void* k,
+                          const void* v, void* o, const uint32_t* mask, const float* bias,
+                          bool dense, hipStream_t st);
+hipError_t launch_s2_f32(const dash_params& p, const Layout& L, const void* q, const void* k,
+                         const void* v, void* o, const uint32_t* mask, const float* bias,
+                         bool dense, hipStream_t st);
+hipError_t launch_decode_s2(const dash_params& p, const Layout& L, const void* q, const void* k,
+                            const void* v, void* o, const uint32_t* mask, const float* bias,
+                            float* partials, bool dense, hipStream_t st);
+
+}  // namespace dash

@@ -1,0 +1,442 @@
+// Stage 1: entmax chunk routing (Sec. 3.2, Eq. 4; Alg. 2) and the routing bias
+// of the prior in the form of Proposition 1.
+//
+// A workgroup owns a tile of 16*MT (token, head) rows of one kv-head: all g_q
+// heads of 16*MT/g_q consecutive tokens, which share one candidate set (the
+// complete chunks before the tokens' own chunk).  It
+//   1. fills an LDS score matrix x[row][chunk] = gamma (alpha-1) <q, kbar> scale,
+//      either with bf16 MFMAs against the exact 3-way bf16 split of the fp32
+//      summaries (products exact, fp32 accumulation: fp32-accurate scores), or by
+//      copying fp32 scores a separate kernel wrote (fp32 inputs, decode);
+//   2. solves sum_c [x_c - tau]_+^(1/(alpha-1)) = 1 per row: one wave per row,
+//      the row spread over the 64 lanes in registers, wave reductions per step;
+//      bracketed Newton from the left end of [max-1, max-n^-(alpha-1)] (the
+//      residual is convex for alpha <= 2) with bisection as the safeguard and as
+//      the only step for alpha > 2;
+//   3. averages the per-head probabilities over the GQA group, takes
+//      mu = mean ln w over the support, d = (ln w - mu)/sigma, and emits the
+//      bit-packed mask plus the compacted (index, bias) list via wave ballots,
+//      appending the diagonal chunk with bias 0 when causal.
+// Nothing of the score matrix ever goes to HBM on the MFMA path.
+#include <math.h>
+
+#include "common.h"
+#include "dash_internal.h"
+
+namespace dash {
+
+struct S1Args {
+  const void* q;
+  const uint16_t* ksplit;
+  const float* scores;
+  uint32_t* mask;
+  int32_t* cnt;
+  int32_t* idx;
+  float* bias;
+  float* tau;
+  int h_q, h_kv, g_q, n_q, block, t_c, t_all, words, pos0, causal, ld;
+  int64_t qs_b, qs_h, qs_t;
+  float xscale, pexp, alpha, inv_sigma;
+};
+
+enum { MODE_P1 = 0, MODE_P2 = 1, MODE_P4 = 2, MODE_GEN = 3, MODE_BISECT = 4 };
+
+// u^p and u^(p-1) for u >= 0 (0 -> 0, and 0 for the derivative term as well)
+template <int MODE>
+__device__ __forceinline__ void pow_terms(float u, float p, float& f, float& g) {
+  if constexpr (MODE == MODE_P1) {
+    f = u; g = u > 0.f ? 1.f : 0.f;
+  } else if constexpr (MODE == MODE_P2) {
+    f = u * u; g = u;
+  } else if constexpr (MODE == MODE_P4) {
+    const float u2 = u * u; g = u2 * u; f = u2 * u2;
+  } else {
+    g = u > 0.f ? exp2f((p - 1.f) * log2f(u)) : 0.f;
+    f = g * u;
+  }
+}
+template <int MODE> __device__ __forceinline__ float pow_p(float u, float p) {
+  float f, g; pow_terms<MODE>(u, p, f, g); return f;
+}
+
+// Solve RB rows at once (interleaved for ILP).  Row values live in registers:
+// lane l holds chunks l, l+64, ...  On exit the rows of S hold the per-head
+// entmax probabilities.
+template <int NJ, int RB, int MODE>
+__device__ __forceinline__ void solve_rows(float* S, int ld, int row0, int n_cand, float alpha,
+                                           float p, int lane, float* tau_out /*[RB]*/) {
+  float v[RB][NJ], mx[RB], lo[RB], hi[RB], tau[RB];
+  bool done[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; rb++) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int c = lane + 64 * j;
+      v[rb][j] = c < n_cand ? S[(row0 + rb) * ld + c] : -INFINITY;
+      m = fmaxf(m, v[rb][j]);
+    }
+    mx[rb] = wave_max(m);
+    lo[rb] = mx[rb] - 1.f;
+    hi[rb] = mx[rb] - exp2f(-(alpha - 1.f) * log2f((float)n_cand));
+    tau[rb] = lo[rb];
+    done[rb] = false;
+  }
+  for (int it = 0; it < 64; it++) {
+    bool all_done = true;
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+      float F = 0.f, G = 0.f;
+#pragma unroll
+      for (int j = 0; j < NJ; j++) {
+        float f, g;
+        pow_terms<MODE>(fmaxf(v[rb][j] - tau[rb], 0.f), p, f, g);
+        F += f; G += g;
+      }
+      F = wave_sum(F);
+      G = wave_sum(G);
+      if (!done[rb]) {
+        const float f = F - 1.f;
+        if (f == 0.f) {
+          done[rb] = true;
+        } else {
+          if (f > 0.f) lo[rb] = tau[rb]; else hi[rb] = tau[rb];
+          const float mid = 0.5f * (lo[rb] + hi[rb]);
+          float cand = (MODE == MODE_BISECT || !(G > 0.f)) ? mid : tau[rb] + f / (p * G);
+          if (MODE != MODE_BISECT && cand == tau[rb]) {
+            done[rb] = true;                       // Newton step below the fp32 spacing of tau
+          } else {
+            if (!(cand > lo[rb] && cand < hi[rb])) cand = mid;
+            if (!(cand > lo[rb] && cand < hi[rb])) {
+              done[rb] = true;                     // bracket closed: adjacent floats
+              tau[rb] = lo[rb];
+            } else {
+              tau[rb] = cand;
+            }
+          }
+        }
+      }
+      all_done = all_done && done[rb];
+    }
+    if (all_done) break;
+  }
+#pragma unroll
+  for (int rb = 0; rb < RB; rb++) {
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      const int c = lane + 64 * j;
+      if (c < n_cand) S[(row0 + rb) * ld + c] = pow_p<MODE>(fmaxf(v[rb][j] - tau[rb], 0.f), p);
+    }
+    tau_out[rb] = tau[rb];
+  }
+}
+
+template <int NJ, int MODE>
+__device__ __forceinline__ void solve_wave_rows(float* S, const S1Args& a, int row_begin, int nrows,
+                                                int n_cand, int lane, int b, int r, int tok0) {
+  constexpr int RB = NJ <= 8 ? 4 : (NJ == 16 ? 2 : 1);
+  for (int rr = 0; rr < nrows; rr += RB) {
+    float t[RB];
+    solve_rows<NJ, RB, MODE>(S, a.ld, row_begin + rr, n_cand, a.alpha, a.pexp, lane, t);
+    if (a.tau && lane == 0) {
+#pragma unroll
+      for (int rb = 0; rb < RB; rb++) {
+        const int row = row_begin + rr + rb;
+        const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
+        if (tok < a.n_q) a.tau[((int64_t)b * a.h_q + head) * a.n_q + tok] = t[rb];
+      }
+    }
+  }
+}
+
+template <int NJ>
+__device__ __forceinline__ void emit_token(const float* S, const S1Args& a, uint32_t* mw, int tl,
+                                           int tok, int n_cand, int lane, int b, int r) {
+  const float inv_g = 1.f / (float)a.g_q;
+  float lw[NJ];
+  float slog = 0.f, nsup = 0.f;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int c = lane + 64 * j;
+    float s = 0.f;
+    if (c < n_cand)
+      for (int h = 0; h < a.g_q; h++) s += S[(tl * a.g_q + h) * a.ld + c];
+    s *= inv_g;
+    lw[j] = s > 0.f ? logf(s) : INFINITY;   // +inf marks "not routed"
+    if (s > 0.f) { slog += lw[j]; nsup += 1.f; }
+  }
+  slog = wave_sum(slog);
+  nsup = wave_sum(nsup);
+  const float mu = nsup > 0.f ? slog / nsup : 0.f;
+  const int64_t base = ((int64_t)b * a.h_kv + r) * a.n_q + tok;
+  int32_t* oidx = a.idx ? a.idx + base * a.t_all : nullptr;
+  float* obias = a.bias + base * a.t_all;
+  for (int wi = lane; wi < a.words; wi += 64) mw[wi] = 0u;
+  __builtin_amdgcn_wave_barrier();
+  int running = 0;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int c = lane + 64 * j;
+    const bool member = lw[j] != INFINITY;
+    const uint64_t bal = __ballot(member);
+    if (lane == 0 && 2 * j < a.words) {
+      mw[2 * j] = (uint32_t)bal;
+      if (2 * j + 1 < a.words) mw[2 * j + 1] = (uint32_t)(bal >> 32);
+    }
+    if (member) {
+      const int pos = running + __popcll(bal & ((1ull << lane) - 1ull));
+      if (oidx) oidx[pos] = c;
+      obias[pos] = (lw[j] - mu) * a.inv_sigma;
+    }
+    running += __popcll(bal);
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (a.causal && lane == 0) {
+    const int cd = (a.pos0 + tok) / a.block;   // the query's own chunk
+    if (oidx) oidx[running] = cd;
+    obias[running] = 0.f;
+    mw[cd >> 5] |= 1u << (cd & 31);
+  }
+  if (a.causal) running += 1;
+  __builtin_amdgcn_wave_barrier();
+  if (a.cnt && lane == 0) a.cnt[base] = running;
+  uint32_t* om = a.mask + base * a.words;
+  for (int wi = lane; wi < a.words; wi += 64) om[wi] = mw[wi];
+  __builtin_amdgcn_wave_barrier();
+}
+
+template <int MT, int D, bool FROM_MFMA>
+__global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
+  extern __shared__ float S[];   // [16*MT][ld] scores, then per-head probabilities
+  __shared__ uint32_t mwords[4][64];
+  constexpr int ROWS = 16 * MT;
+  const int tokt = ROWS / a.g_q;
+  const int tile = gridDim.x - 1 - blockIdx.x;   // longest rows first
+  const int r = blockIdx.y, b = blockIdx.z;
+  const int tok0 = tile * tokt;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int n_cand = a.causal ? (a.pos0 + tok0) / a.block : a.t_c;
+  if (n_cand > a.t_c) n_cand = a.t_c;
+
+  if (n_cand > 0) {
+    if constexpr (FROM_MFMA) {
+      const int m = lane & 15, kq = lane >> 4;
+      bf16x8 qf[MT][D / 32];
+#pragma unroll
+      for (int mt = 0; mt < MT; mt++) {
+        const int row = mt * 16 + m;
+        const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
+        const uint16_t* qp = (const uint16_t*)a.q + b * a.qs_b + head * a.qs_h +
+                             (int64_t)(tok < a.n_q ? tok : a.n_q - 1) * a.qs_t + kq * 8;
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ks++)
+          qf[mt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 32);
+      }
+      const int ntile_c = (n_cand + 15) >> 4;
+      for (int ct = wave; ct < ntile_c; ct += 4) {
+        const int c = ct * 16 + m;
+        const int cl = c < n_cand ? c : n_cand - 1;
+        const uint16_t* kp = a.ksplit + (((int64_t)b * a.h_kv + r) * a.t_c + cl) * 3 * D + kq * 8;
+        f32x4 acc_hi[MT], acc_lo[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) { acc_hi[mt] = f32x4{0, 0, 0, 0}; acc_lo[mt] = f32x4{0, 0, 0, 0}; }
+#pragma unroll
+        for (int ks = 0; ks < D / 32; ks++) {
+          const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(kp + ks * 32);
+          const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(kp + D + ks * 32);
+          const bf16x8 k2 = *reinterpret_cast<const bf16x8*>(kp + 2 * D + ks * 32);
+#pragma unroll
+          for (int mt = 0; mt < MT; mt++) {
+            acc_hi[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], k0, acc_hi[mt], 0, 0, 0);
+            acc_lo[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], k1, acc_lo[mt], 0, 0, 0);
+            acc_lo[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], k2, acc_lo[mt], 0, 0, 0);
+          }
+        }
+        if (c < n_cand) {
+#pragma unroll
+          for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+              S[(mt * 16 + 4 * kq + j) * a.ld + c] = (acc_hi[mt][j] + acc_lo[mt][j]) * a.xscale;
+        }
+      }
+    } else {
+      for (int row = wave; row < ROWS; row += 4) {
+        const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
+        const float* src = a.scores + (((int64_t)b * a.h_q + head) * a.n_q + (tok < a.n_q ? tok : 0)) * a.t_c;
+        const bool ok = tok < a.n_q;
+        for (int c = lane; c < n_cand; c += 64) S[row * a.ld + c] = ok ? src[c] : 0.f;
+      }
+    }
+  }
+  __syncthreads();
+
+  const int nj = (n_cand + 63) >> 6;
+  if (n_cand > 0) {
+    const int rpw = ROWS / 4, row_begin = wave * rpw;
+    int mode;
+    if (a.pexp < 1.f) mode = MODE_BISECT;
+    else if (a.pexp == 1.f) mode = MODE_P1;
+    else if (a.pexp == 2.f) mode = MODE_P2;
+    else if (a.pexp == 4.f) mode = MODE_P4;
+    else mode = MODE_GEN;
+#define DASH_SOLVE(NJ_)                                                                          \
+  switch (mode) {                                                                                \
+    case MODE_P1: solve_wave_rows<NJ_, MODE_P1>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
+    case MODE_P2: solve_wave_rows<NJ_, MODE_P2>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
+    case MODE_P4: solve_wave_rows<NJ_, MODE_P4>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
+    case MODE_GEN: solve_wave_rows<NJ_, MODE_GEN>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
+    default: solve_wave_rows<NJ_, MODE_BISECT>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
+  }
+    if (nj <= 1) { DASH_SOLVE(1) }
+    else if (nj <= 2) { DASH_SOLVE(2) }
+    else if (nj <= 4) { DASH_SOLVE(4) }
+    else if (nj <= 8) { DASH_SOLVE(8) }
+    else if (nj <= 16) { DASH_SOLVE(16) }
+    else { DASH_SOLVE(32) }
+#undef DASH_SOLVE
+  } else if (a.tau) {
+    for (int row = threadIdx.x; row < ROWS; row += 256) {
+      const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
+      if (tok < a.n_q) a.tau[((int64_t)b * a.h_q + head) * a.n_q + tok] = 0.f;
+    }
+  }
+  __syncthreads();
+
+  for (int tl = wave; tl < tokt; tl += 4) {
+    const int tok = tok0 + tl;
+    if (tok >= a.n_q) break;
+    uint32_t* mw = mwords[wave];
+    if (nj <= 1) emit_token<1>(S, a, mw, tl, tok, n_cand, lane, b, r);
+    else if (nj <= 2) emit_token<2>(S, a, mw, tl, tok, n_cand, lane, b, r);
+    else if (nj <= 4) emit_token<4>(S, a, mw, tl, tok, n_cand, lane, b, r);
+    else if (nj <= 8) emit_token<8>(S, a, mw, tl, tok, n_cand, lane, b, r);
+    else if (nj <= 16) emit_token<16>(S, a, mw, tl, tok, n_cand, lane, b, r);
+    else emit_token<32>(S, a, mw, tl, tok, n_cand, lane, b, r);
+  }
+}
+
+// fp32 scores for fp32 inputs and for decode: one 16-lane DPP row per chunk,
+// coalesced float4 reads of the fp32 summaries, fp32 FMA, row reduction.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void s1_scores_f32_kernel(
+    const T* __restrict__ q, const float* __restrict__ kbar, float* __restrict__ scores, int h_q,
+    int h_kv, int g_q, int n_q, int block, int t_c, int pos0, int causal, int64_t qs_b,
+    int64_t qs_h, int64_t qs_t, float xscale) {
+  const int tok = blockIdx.y;
+  const int b = blockIdx.z / h_kv, r = blockIdx.z % h_kv;
+  int n_cand = causal ? (pos0 + tok) / block : t_c;
+  if (n_cand > t_c) n_cand = t_c;
+  const int c0 = blockIdx.x * 16;
+  if (c0 >= n_cand) return;
+  const int cl = threadIdx.x >> 4, l16 = threadIdx.x & 15;
+  const int c = c0 + cl;
+  const float* kp = kbar + (((int64_t)b * h_kv + r) * t_c + (c < n_cand ? c : n_cand - 1)) * D + 4 * l16;
+  float kk[D / 64][4];
+#pragma unroll
+  for (int i = 0; i < D / 64; i++) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(kp + 64 * i);
+    kk[i][0] = t[0]; kk[i][1] = t[1]; kk[i][2] = t[2]; kk[i][3] = t[3];
+  }
+  for (int h = 0; h < g_q; h++) {
+    const int head = r * g_q + h;
+    const T* qp = q + b * qs_b + head * qs_h + (int64_t)tok * qs_t + 4 * l16;
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 64; i++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) acc = fmaf(elem<T>::ld(qp + 64 * i + e), kk[i][e], acc);
+    acc = row16_sum(acc);
+    if (l16 == 0 && c < n_cand)
+      scores[(((int64_t)b * h_q + head) * n_q + tok) * t_c + c] = acc * xscale;
+  }
+}
+
+hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const void* q,
+                                const float* kbar, float* scores, hipStream_t st) {
+  if (L.t_c == 0) return hipSuccess;
+  dim3 grid((L.t_c + 15) / 16, p.n_q, p.batch * p.h_kv), blk(256);
+#define DASH_SC(T_, D_)                                                                           \
+  hipLaunchKernelGGL((s1_scores_f32_kernel<T_, D_>), grid, blk, 0, st, (const T_*)q, kbar, scores, \
+                     p.h_q, p.h_kv, L.g_q, p.n_q, p.block_size, L.t_c, L.pos0, p.causal,          \
+                     p.q_stride[0], p.q_stride[1], p.q_stride[2], L.xscale)
+  if (p.dtype == DASH_BF16) {
+    if (p.head_dim == 128) DASH_SC(uint16_t, 128); else DASH_SC(uint16_t, 64);
+  } else {
+    if (p.head_dim == 128) DASH_SC(float, 128); else DASH_SC(float, 64);
+  }
+#undef DASH_SC
+  return hipGetLastError();
+}
+
+template <typename K>
+static hipError_t launch_route_k(K kern, const S1Args& a, dim3 grid, size_t lds, hipStream_t st) {
+  if (lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
+  return hipGetLastError();
+}
+
+// Exact 3-way bf16 split of the fp32 summaries: x = hi + mid + lo with every piece
+// obtained by truncation (same sign, no rounding), laid out [chunk][3][d].
+__global__ __launch_bounds__(256) void ksplit_kernel(const float* __restrict__ kbar,
+                                                     uint16_t* __restrict__ ksplit, int64_t n_rows,
+                                                     int d) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n_rows * d) return;
+  const int64_t row = i / d;
+  const int col = (int)(i % d);
+  const float x = kbar[i];
+  const uint32_t hi = __float_as_uint(x) & 0xffff0000u;
+  const float r1 = x - __uint_as_float(hi);
+  const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+  const float r2 = r1 - __uint_as_float(mid);
+  uint16_t* o = ksplit + row * 3 * d + col;
+  o[0] = (uint16_t)(hi >> 16);
+  o[d] = (uint16_t)(mid >> 16);
+  o[2 * d] = (uint16_t)(__float_as_uint(r2) >> 16);
+}
+
+hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q, const float* kbar,
+                           uint16_t* ksplit, const float* scores, const S1Out& out, hipStream_t st) {
+  if (ksplit != nullptr && L.t_c > 0) {
+    const int64_t n_rows = (int64_t)p.batch * p.h_kv * L.t_c;
+    const int64_t n = n_rows * p.head_dim;
+    hipLaunchKernelGGL(ksplit_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, kbar,
+                       ksplit, n_rows, p.head_dim);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  S1Args a;
+  a.q = q; a.ksplit = ksplit; a.scores = scores;
+  a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
+  a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.block = p.block_size;
+  a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal;
+  a.ld = ((L.t_c + 15) / 16) * 16 + 4;
+  a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
+  a.xscale = L.xscale; a.pexp = L.pexp; a.alpha = p.alpha; a.inv_sigma = 1.f / p.sigma;
+  const bool mfma = L.use_mfma && ksplit != nullptr;
+  int mt = 1;
+  if (mfma) {
+    if ((size_t)64 * a.ld * 4 <= 65536) mt = 4;
+    else if ((size_t)32 * a.ld * 4 <= 81920) mt = 2;
+  }
+  const int tokt = 16 * mt / L.g_q;
+  dim3 grid((p.n_q + tokt - 1) / tokt, p.h_kv, p.batch);
+  const size_t lds = (size_t)16 * mt * a.ld * 4;
+  if (!mfma) {
+    if (p.head_dim == 128) return launch_route_k(s1_route_kernel<1, 128, false>, a, grid, lds, st);
+    return launch_route_k(s1_route_kernel<1, 64, false>, a, grid, lds, st);
+  }
+#define DASH_RT(MT_)                                                                     \
+  (p.head_dim == 128 ? launch_route_k(s1_route_kernel<MT_, 128, true>, a, grid, lds, st) \
+                     : launch_route_k(s1_route_kernel<MT_, 64, true>, a, grid, lds, st))
+  if (mt == 4) return DASH_RT(4);
+  if (mt == 2) return DASH_RT(2);
+  return DASH_RT(1);
+#undef DASH_RT
+}
+
+}  // namespace dash

@@ -1,0 +1,201 @@
+"""GPU parity tests: the HIP library (through the C ABI) against the fp64 oracle,
+element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dash_oracle as orc
+from paper_2605_18753_amd import binding as B
+from paper_2605_18753_amd.inputs import C1, C2, C3, C5, Workload, make_inputs, shrink
+
+import parity_util as U
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def gen(w):
+    q, k, v = make_inputs(w, "cpu")
+    return q.to(DEV), k.to(DEV), v.to(DEV)
+
+
+@pytest.mark.parametrize("dtype,d,block,n", [("bf16", 128, 64, 1000), ("bf16", 64, 128, 1024),
+                                              ("fp32", 64, 64, 640), ("fp32", 128, 128, 900)])
+def test_kbar_bit_exact(dtype, d, block, n):
+    w = Workload("kbar", 2, 4, 2, n, n, d, block, dtype=dtype)
+    q, k, v = gen(w)
+    p = B.make_params(q, k, v, None, block)
+    kbar = torch.zeros(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    B.dash_kbar_compress(p, k, kbar)
+    torch.cuda.synchronize()
+    ref = orc.block_mean_summaries(U.to_np(k), block).astype(np.float32)
+    assert np.array_equal(kbar.cpu().numpy(), ref)
+    # partial update: only chunk 1 is rewritten
+    kbar2 = torch.full_like(kbar, 7.0)
+    B.dash_kbar_compress(p, k, kbar2, 1, 1)
+    torch.cuda.synchronize()
+    got = kbar2.cpu().numpy()
+    assert np.array_equal(got[:, :, 1], ref[:, :, 1]) and np.all(got[:, :, 0] == 7.0)
+
+
+def test_prefill_c1_fp32_full():
+    w = C1
+    q, k, v = gen(w)
+    run = U.run_prefill(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run)
+    print(f"C1: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e} "
+          f"tau_err {rep.worst_tau_err:.2e} bias_err {rep.worst_bias_err:.2e}")
+    assert 0.05 < rep.sparsity < 0.95
+
+
+SMALL = [
+    # name, batch, h_q, h_kv, n, d, block, extra
+    ("gqa4_ragged", 1, 8, 2, 1000, 128, 64, {}),
+    ("gqa1_needles", 2, 2, 2, 640, 128, 64, {"needles": 2, "offset_sigma": 0.0}),
+    ("gqa16_b128_d64", 1, 16, 1, 1536, 64, 128, {}),
+    ("gqa2_alpha2", 1, 4, 2, 777, 128, 64, {"alpha": 2.0}),
+    ("gqa4_alpha125", 1, 4, 1, 1024, 128, 64, {"alpha": 1.25, "offset_sigma": 1.0}),
+    ("gqa4_alpha17", 1, 4, 1, 900, 128, 64, {"alpha": 1.7}),
+    ("gqa4_alpha3_bisect", 1, 4, 1, 900, 128, 64, {"alpha": 3.0}),
+    ("gqa8_sigma10", 1, 8, 1, 1100, 128, 64, {"sigma": 10.0}),
+    ("gqa4_sigma1e8_gamma", 1, 8, 2, 1300, 128, 64, {"sigma": 1e8, "gamma": 1.5}),
+    ("single_chunk", 1, 4, 1, 50, 128, 64, {}),
+    ("exactly_one_block", 1, 4, 1, 64, 64, 64, {}),
+    ("noncausal_bf16", 1, 4, 2, 768, 128, 64, {"causal": False}),
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_prefill_bf16_small(case):
+    name, batch, h_q, h_kv, n, d, block, extra = case
+    w = Workload(name, batch, h_q, h_kv, n, n, d, block, seed=3, **extra)
+    q, k, v = gen(w)
+    run = U.run_prefill(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run)
+    print(f"{name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e} "
+          f"tau_err {rep.worst_tau_err:.2e} bias_err {rep.worst_bias_err:.2e}")
+
+
+@pytest.mark.parametrize("case", [("fp32_gqa2", 1, 4, 2, 500, 64, 64, {}),
+                                  ("fp32_gqa4_d128_b128", 2, 4, 1, 700, 128, 128, {"alpha": 2.0}),
+                                  ("fp32_noncausal_sigma", 1, 2, 1, 512, 128, 64, {"causal": False, "sigma": 4.0})],
+                         ids=lambda c: c[0])
+def test_prefill_fp32_small(case):
+    name, batch, h_q, h_kv, n, d, block, extra = case
+    w = Workload(name, batch, h_q, h_kv, n, n, d, block, dtype="fp32", seed=5, **extra)
+    q, k, v = gen(w)
+    run = U.run_prefill(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run)
+    print(f"{name}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+
+
+@pytest.mark.parametrize("dtype,causal,n,d,hq,hkv", [("bf16", True, 1000, 128, 8, 2), ("bf16", False, 700, 64, 2, 2),
+                                                      ("fp32", True, 300, 64, 2, 1), ("fp32", False, 256, 128, 4, 1),
+                                                      ("bf16", True, 2100, 128, 16, 1)])
+def test_dense_attn(dtype, causal, n, d, hq, hkv):
+    w = Workload("dense", 2, hq, hkv, n, n, d, 64, dtype=dtype, causal=causal, seed=11)
+    q, k, v = gen(w)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, 64, causal=causal)
+    ws = B.alloc_workspace(p, DEV)
+    B.dense_attn(p, q, k, v, o, ws)
+    torch.cuda.synchronize()
+    qn, kn, vn = U.to_np(q), U.to_np(k), U.to_np(v)
+    g = hq // hkv
+    worst = 0.0
+    for b in range(2):
+        for h in range(hq):
+            ref = orc.dense_attention(qn[b, h], kn[b, h // g], vn[b, h // g], 1.0 / np.sqrt(d), causal)
+            worst = max(worst, np.abs(U.to_np(o)[b, h] - ref).max() / np.abs(ref).max())
+    assert worst <= (2e-2 if dtype == "bf16" else 1e-5), worst
+
+
+@pytest.mark.parametrize("n_kv,extra", [(3000, {}), (4096, {}), (700, {"alpha": 2.0}), (63, {}), (2049, {"sigma": 1e8})])
+def test_decode_small(n_kv, extra):
+    w = Workload("decode", 3, 8, 2, 1, n_kv, 128, 64, offset_sigma=0.7, seed=9, **extra)
+    q, k, v = gen(w)
+    run = U.run_decode(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run)
+    print(f"decode {n_kv}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+
+
+def test_decode_updates_summary_cache_when_chunk_completes():
+    w = Workload("decode_cache", 2, 4, 2, 1, 1024, 128, 64, offset_sigma=0.7, seed=2)
+    q, k, v = gen(w)
+    p = B.make_params(q, k, v, None, 64)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    B.dash_kbar_compress(p, k, kbar)
+    stale = kbar.clone()
+    stale[:, :, -1] = 123.0                  # the chunk the current token completes
+    run = U.run_decode(w, q, k, v, stale)
+    assert torch.equal(stale, kbar)          # rewritten in place, the rest untouched
+    U.check_against_oracle(w, q, k, v, run)
+
+
+def test_split_stages_match_fused_call():
+    w = Workload("stages", 1, 8, 2, 900, 900, 128, 64, seed=4)
+    q, k, v = gen(w)
+    fused = U.run_prefill(w, q, k, v)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, 64)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    ws = B.alloc_workspace(p, DEV)
+    B.dash_kbar_compress(p, k, kbar)
+    B.dash_stage1_route(p, q, kbar, B.Lists(), ws)          # lists stay in the workspace
+    B.dash_stage2_attend(p, q, k, v, o, B.Lists(), ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o, fused.o)
+    # rerun: bitwise deterministic
+    again = U.run_prefill(w, q, k, v)
+    assert torch.equal(again.o, fused.o) and torch.equal(again.lists.mask, fused.lists.mask)
+
+
+# ---- larger shapes with real sparsity: sampled rows -------------------------
+def gen_dev(w):
+    return make_inputs(w, DEV)
+
+
+@pytest.mark.parametrize("case", [
+    ("mid_gqa4_8k", 1, 8, 2, 8192, 128, 64, {}),
+    ("mid_gqa4_8k_sparse", 1, 8, 2, 8192, 128, 64, {"gamma": 1.5, "offset_sigma": 0.7}),
+    ("mid_b128_16k", 1, 4, 1, 16384, 128, 128, {"alpha": 2.0}),
+    ("mid_needles_gqa1", 2, 2, 2, 8192, 128, 64, {"needles": 4, "offset_sigma": 0.0}),
+], ids=lambda c: c[0])
+def test_prefill_mid_sampled(case):
+    name, batch, h_q, h_kv, n, d, block, extra = case
+    w = Workload(name, batch, h_q, h_kv, n, n, d, block, seed=1, **extra)
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 160))
+    print(f"{name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e} "
+          f"tau_err {rep.worst_tau_err:.2e}")
+    assert rep.sparsity > 0.2
+
+
+def test_prefill_c2_full_size_sampled():
+    w = C2
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96, heads=[(0, 0), (0, 5), (0, 7)]))
+    print(f"C2 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+
+
+def test_prefill_c5_full_size_sampled():
+    w = C5
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96, heads=[(0, 0), (1, 9), (3, 15)]))
+    print(f"C5 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+
+
+def test_decode_c3_full_size_sampled():
+    w = C3
+    q, k, v = gen_dev(w)
+    run = U.run_decode(w, q, k, v)
+    rows = [(b, r, 0) for (b, r) in [(0, 0), (3, 5), (9, 2), (15, 7)]]
+    rep, err = U.check_against_oracle(w, q, k, v, run, rows)
+    print(f"C3 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    # every (batch, kv-head) row: the list is well formed and the output finite
+    cnt = run.lists.cnt.cpu().numpy()
+    assert cnt.min() >= 1 and cnt.max() <= 2048
+    assert torch.isfinite(run.o.float()).all()

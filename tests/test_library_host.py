@@ -1,0 +1,97 @@
+"""CPU-side tests of the C-ABI library: it loads, exports every symbol the header
+declares, sizes its workspace, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_18753_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def params(**kw):
+    p = B.dash_params()
+    base = dict(batch=1, h_q=8, h_kv=2, n_q=1024, n_kv=1024, head_dim=128, block_size=64, causal=1,
+                dtype=B.DASH_BF16, alpha=1.5, gamma=1.0, sigma=1.0, scale=0.0)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(p, k, v)
+    for name, heads, n in (("q_stride", p.h_q, p.n_q), ("k_stride", p.h_kv, p.n_kv),
+                           ("v_stride", p.h_kv, p.n_kv), ("o_stride", p.h_q, p.n_q)):
+        getattr(p, name)[:] = [heads * n * p.head_dim, n * p.head_dim, p.head_dim]
+    return p
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "dash_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(dash_\w+|dense_attn)\s*\(", text))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = header_functions()
+    assert {"dash_attn_prefill", "dash_attn_decode", "dense_attn", "dash_kbar_compress"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert names == set(B.exported_symbols())
+
+
+def test_workspace_and_list_sizes():
+    p = params()
+    assert B.list_stride(p) == 16 and B.mask_words(p) == 1
+    n = B.workspace_bytes(p)
+    rows = 2 * 1024
+    assert n >= rows * 16 * 4 + rows * 4 + 2 * 16 * 3 * 128 * 2
+    p2 = params(n_q=1000, n_kv=1000)          # ragged tail: 15 complete chunks + 1 partial
+    assert B.list_stride(p2) == 16
+    pd = params(n_q=1, n_kv=131072, batch=16, h_q=32, h_kv=8)
+    assert B.list_stride(pd) == 2048 and B.mask_words(pd) == 64
+    assert B.workspace_bytes(pd) > 16 * 32 * 2047 * 4
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(h_q=7), -1), (dict(alpha=1.0), -1), (dict(alpha=0.5), -1), (dict(sigma=0.0), -1),
+    (dict(gamma=-1.0), -1), (dict(batch=0), -1), (dict(n_q=2048), -1), (dict(causal=2), -1),
+    (dict(dtype=3), -1), (dict(causal=0, n_q=1000, n_kv=1000), -1),
+    (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(h_q=64, h_kv=2), -2),
+    (dict(n_q=100, n_kv=1001), -2), (dict(n_q=262144, n_kv=262144), -2),
+])
+def test_invalid_parameters_are_rejected(kw, code):
+    lib = B.load_library()
+    p = params(**kw)
+    # every compute entry point rejects the same way, before any launch
+    assert lib.dash_attn_prefill(ctypes.byref(p), 256, 256, 256, 256, 256, None, None, None, None, None,
+                                 256, 1 << 40, None) == code
+    assert lib.dash_stage1_route(ctypes.byref(p), 256, 256, None, None, None, None, None,
+                                 256, 1 << 40, None) == code
+    if not (kw.get("causal") == 0 and len(kw) == 3):     # ragged non-causal is fine for dense
+        n = ctypes.c_size_t(0)
+        assert lib.dash_attn_workspace_bytes(ctypes.byref(p), ctypes.byref(n)) == code
+        assert lib.dense_attn(ctypes.byref(p), 1, 1, 1, 1, 256, 1 << 40, None) == code
+
+
+def test_null_and_workspace_errors():
+    lib = B.load_library()
+    p = params()
+    need = B.workspace_bytes(p)
+    assert lib.dense_attn(ctypes.byref(p), None, 1, 1, 1, 256, need, None) == -1
+    assert lib.dense_attn(ctypes.byref(p), 256, 256, 256, 256, None, need, None) == -3
+    assert lib.dense_attn(ctypes.byref(p), 256, 256, 256, 256, 256, need - 1, None) == -3
+    assert lib.dense_attn(ctypes.byref(p), 256, 256, 256, 256, 257, need, None) == -3     # misaligned
+    assert lib.dash_attn_prefill(ctypes.byref(p), 256, 256, 256, 256, None, None, None, None, None, None,
+                                 256, need, None) == -1                                  # kbar is required
+    assert lib.dash_attn_decode(ctypes.byref(p), 256, 256, 256, 256, 256, None, None, None, None, None,
+                                256, need, None) == -1                                   # n_q must be 1
+    assert lib.dash_attn_workspace_bytes(None, None) == -1
+    p.q_stride[2] = 100                                                                    # misaligned rows
+    assert lib.dense_attn(ctypes.byref(p), 256, 256, 256, 256, 256, need, None) == -1
+
+
+def test_strerror():
+    lib = B.load_library()
+    assert lib.dash_strerror(0) == b"ok"
+    for c in (-1, -2, -3, -4, 17):
+        assert len(lib.dash_strerror(c)) > 0
