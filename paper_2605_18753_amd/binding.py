@@ -16,7 +16,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdash_attn.so")
+LIB_PATH = os.environ.get("DASH_ATTN_LIB") or os.path.join(_HERE, "libdash_attn.so")
 
 DASH_F32, DASH_BF16 = 0, 1
 

@@ -23,9 +23,18 @@
 // bf16 register transpose per thread).  Row max / row sum are in-lane plus one
 // cross-half exchange, and the O rescale is a per-lane scalar.
 #include <math.h>
+#include <stdlib.h>
+
+#include <type_traits>
 
 #include "common.h"
 #include "dash_internal.h"
+
+// Two workgroups (8 waves) per CU: with <= 256 VGPRs per wave a second wave per
+// SIMD overlaps its softmax VALU work with the other wave's MFMAs.
+#ifndef DASH_S2_MIN_WG
+#define DASH_S2_MIN_WG 2
+#endif
 
 namespace dash {
 
@@ -37,6 +46,8 @@ struct S2Args {
   float c1;   // scale * log2(e)
   float* part;   // decode partials
 };
+
+constexpr float kLazy = 8.f;   // lazy-rescale slack, in base-2 logit units
 
 template <int D> struct S2Cfg {
   static constexpr int KLD = D + 8;          // bf16 elements per K row in LDS
@@ -54,14 +65,19 @@ __device__ __forceinline__ int slot_group_key(int sg, int i) {
   return (sg >> 1) * 16 + (i >> 2) * 8 + (sg & 1) * 4 + (i & 3);
 }
 
+// RT: 32-row tiles per wave (1 or 2).  A wave owns 32*RT (token, head) rows; the
+// K / V^T fragments it reads from LDS are reused for its RT row tiles, so RT = 2
+// halves the LDS traffic per MFMA flop.
+//
 // DECODE: one query token per sequence (n_q == 1).  All four waves hold the same
 // g_q rows and compute the same S^T; wave w accumulates only the d-tile w of
 // O^T.  The workgroup handles the `split`-th share of the token's attended
 // chunks and writes an unnormalised partial (O, running max, running sum) that
 // a merge kernel combines (split-KV decoding, Sec. 3.5).
-template <int D, bool DENSE, bool DECODE>
-__global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
+template <int D, int RT, bool DENSE, bool DECODE>
+__global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a) {
   using C = S2Cfg<D>;
+  static_assert(!DECODE || RT == 1, "decode uses one row tile");
   extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
   uint16_t* Ks = lds;                               // [2][64][KLD]
   uint16_t* Vt = lds + 2 * C::K_ELEMS;              // [2][D][VLD]
@@ -75,26 +91,34 @@ __global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
   const int hbi = blockIdx.x % a.hb;
   const int tile = a.n_tiles - 1 - blockIdx.x / a.hb;   // longest rows first; DECODE: split id
   const int r = hbi % a.h_kv, b = hbi / a.h_kv;
-  const int tokw = DECODE ? 1 : 32 / a.g_q;         // tokens per wave
+  constexpr int WROWS = 32 * RT;                    // rows per wave
+  const int tokw = DECODE ? 1 : WROWS / a.g_q;      // tokens per wave
   const int tok_w0 = DECODE ? 0 : tile * 4 * tokw + wave * tokw;   // first token of this wave
   const int nsub = a.block >> 6;
 
-  // ---- per-row constants -------------------------------------------------
-  const int my_tok = DECODE ? 0 : tok_w0 + n / a.g_q;
-  const int my_head = r * a.g_q + n % a.g_q;
-  const bool row_ok = DECODE ? n < a.g_q : my_tok < a.n_q;
-  const int row_pos = a.pos0 + (row_ok ? my_tok : a.n_q - 1);
-  // chunk of the wave's tokens (all tokens of a granule share it)
+  // ---- per-row constants (row tile rt, row n of it) -----------------------
+  int my_tok[RT], my_head[RT], row_pos[RT];
+  bool row_ok[RT];
+#pragma unroll
+  for (int rt = 0; rt < RT; rt++) {
+    const int row = rt * 32 + n;
+    my_tok[rt] = DECODE ? 0 : tok_w0 + row / a.g_q;
+    my_head[rt] = r * a.g_q + row % a.g_q;
+    row_ok[rt] = DECODE ? row < a.g_q : my_tok[rt] < a.n_q;
+    row_pos[rt] = a.pos0 + (row_ok[rt] ? my_tok[rt] : a.n_q - 1);
+  }
+  // chunk of the wave's tokens (all tokens of a wave share it)
   const int cw = (a.pos0 + (tok_w0 < a.n_q ? tok_w0 : a.n_q - 1)) / a.block;
   const bool wave_ok = tok_w0 < a.n_q;
 
   // ---- Q fragments (operand B of S^T = K Q^T) ----------------------------
-  bf16x8 qf[D / 16];
-  {
-    const uint16_t* qp = a.q + b * a.qs_b + my_head * a.qs_h +
-                         (int64_t)(row_ok ? my_tok : a.n_q - 1) * a.qs_t + h * 8;
+  bf16x8 qf[RT][D / 16];
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  for (int rt = 0; rt < RT; rt++) {
+    const uint16_t* qp = a.q + b * a.qs_b + my_head[rt] * a.qs_h +
+                         (int64_t)(row_ok[rt] ? my_tok[rt] : a.n_q - 1) * a.qs_t + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) qf[rt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
   // ---- chunk bitmaps -------------------------------------------------------
@@ -184,41 +208,65 @@ __global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
   };
 
   // ---- staging -------------------------------------------------------------
+  // Threads 0..127 stage K (row-major copy), threads 128..255 stage V (8x8 bf16
+  // register transpose into the permuted V^T layout).  Every load address is
+  // "uniform tile base + uniform per-load stride + per-thread byte offset", so the
+  // per-tile address arithmetic is scalar.
   const bool stage_k = tid < 128;
   const int st = tid & 127;
-  const uint16_t* kbase = a.k + b * a.ks_b + r * a.ks_h;
-  const uint16_t* vbase = a.v + b * a.vs_b + r * a.vs_h;
+  const char* kbase = reinterpret_cast<const char*>(a.k + b * a.ks_b + r * a.ks_h);
+  const char* vbase = reinterpret_cast<const char*>(a.v + b * a.vs_b + r * a.vs_h);
   u32x4 sreg[8];
   const int v_sg = st & 7, v_dg = st >> 3;          // V: slot group, 8-column group
+  constexpr int KROWS = 128 / (D / 8);              // K rows covered by one load of the 128 threads
+  const int k_row0 = st / (D / 8), k_col = (st % (D / 8)) * 8;
+  const int v_row0 = (v_sg >> 1) * 16 + (v_sg & 1) * 4;
+  const uint32_t k_toff = (uint32_t)(k_row0 * a.ks_t + k_col) * 2u;     // bytes
+  const uint32_t v_toff = (uint32_t)(v_row0 * a.vs_t + v_dg * 8) * 2u;
+  const bool v_active = v_dg < D / 8;
   auto stage_load = [&](int u, int sub) {
     const int kpos0 = u * a.block + sub * 64;
-    if (stage_k) {
+    if (kpos0 + 64 <= a.n_kv) {
+      if (stage_k) {
+        const char* tb = kbase + (int64_t)kpos0 * a.ks_t * 2;
 #pragma unroll
-      for (int i = 0; i < C::K_LOADS; i++) {
-        const int pid = i * 128 + st;
-        int key = kpos0 + pid / (D / 8);
-        key = key < a.n_kv ? key : a.n_kv - 1;
-        sreg[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * a.ks_t + (pid % (D / 8)) * 8);
+        for (int i = 0; i < C::K_LOADS; i++)
+          sreg[i] = *reinterpret_cast<const u32x4*>(tb + (int64_t)i * KROWS * a.ks_t * 2 + k_toff);
+      } else if (v_active) {
+        const char* tb = vbase + (int64_t)kpos0 * a.vs_t * 2;
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+          sreg[i] = *reinterpret_cast<const u32x4*>(tb + (int64_t)((i >> 2) * 8 + (i & 3)) * a.vs_t * 2 + v_toff);
       }
-    } else if (v_dg < D / 8) {
+    } else {
+      // ragged last tile: clamp the row index (those keys are masked later)
+      if (stage_k) {
 #pragma unroll
-      for (int i = 0; i < 8; i++) {
-        int key = kpos0 + slot_group_key(v_sg, i);
-        key = key < a.n_kv ? key : a.n_kv - 1;
-        sreg[i] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)key * a.vs_t + v_dg * 8);
+        for (int i = 0; i < C::K_LOADS; i++) {
+          int key = kpos0 + i * KROWS + k_row0;
+          key = key < a.n_kv ? key : a.n_kv - 1;
+          sreg[i] = *reinterpret_cast<const u32x4*>(kbase + ((int64_t)key * a.ks_t + k_col) * 2);
+        }
+      } else if (v_active) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+          int key = kpos0 + slot_group_key(v_sg, i);
+          key = key < a.n_kv ? key : a.n_kv - 1;
+          sreg[i] = *reinterpret_cast<const u32x4*>(vbase + ((int64_t)key * a.vs_t + v_dg * 8) * 2);
+        }
       }
     }
   };
+  uint16_t* const k_dst0 = Ks + k_row0 * C::KLD + k_col;
+  uint16_t* const v_dst0 = Vt + (v_dg * 8) * C::VLD + v_sg * 8;
   auto stage_store = [&](int buf) {
     if (stage_k) {
-      uint16_t* dst = Ks + buf * C::K_ELEMS;
+      uint16_t* dst = k_dst0 + buf * C::K_ELEMS;
 #pragma unroll
-      for (int i = 0; i < C::K_LOADS; i++) {
-        const int pid = i * 128 + st;
-        *reinterpret_cast<u32x4*>(dst + (pid / (D / 8)) * C::KLD + (pid % (D / 8)) * 8) = sreg[i];
-      }
-    } else if (v_dg < D / 8) {
-      uint16_t* dst = Vt + buf * C::V_ELEMS + (v_dg * 8) * C::VLD + v_sg * 8;
+      for (int i = 0; i < C::K_LOADS; i++)
+        *reinterpret_cast<u32x4*>(dst + i * KROWS * C::KLD) = sreg[i];
+    } else if (v_active) {
+      uint16_t* dst = v_dst0 + buf * C::V_ELEMS;
       // 8x8 bf16 transpose: column e of the 8 loaded rows becomes one 16-byte row
 #pragma unroll
       for (int e = 0; e < 8; e++) {
@@ -226,23 +274,30 @@ __global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
 #pragma unroll
         for (int i2 = 0; i2 < 4; i2++) {
           const uint32_t lo = sreg[2 * i2][e >> 1], hi = sreg[2 * i2 + 1][e >> 1];
-          o[i2] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+          // byte select: low halves {hi[1:0], lo[1:0]} or high halves {hi[3:2], lo[3:2]}
+          o[i2] = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
         }
         *reinterpret_cast<u32x4*>(dst + e * C::VLD) = o;
       }
     }
   };
 
-  // ---- online-softmax state ----------------------------------------------
-  float m_run = -INFINITY, l_run = 0.f;
+  // ---- online-softmax state (base-2 logits) -------------------------------
+  float m_run[RT], l_run[RT];
   constexpr int NDT = DECODE ? 1 : D / 32;
-  f32x16 oacc[NDT];
+  f32x16 oacc[RT][NDT];
 #pragma unroll
-  for (int dt = 0; dt < NDT; dt++)
+  for (int rt = 0; rt < RT; rt++) {
+    m_run[rt] = -INFINITY; l_run[rt] = 0.f;
 #pragma unroll
-    for (int j = 0; j < 16; j++) oacc[dt][j] = 0.f;
+    for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+      for (int j = 0; j < 16; j++) oacc[rt][dt][j] = 0.f;
+  }
 
-  float bias_row = 0.f;   // bias * log2e of this lane's row for the current chunk
+  float bias_row[RT];   // bias * log2e of this lane's rows for the current chunk
+#pragma unroll
+  for (int rt = 0; rt < RT; rt++) bias_row[rt] = 0.f;
   bool wave_on = false, diag = false;
 
   auto begin_chunk = [&](int u) {
@@ -262,74 +317,104 @@ __global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
         }
       }
     }
-    bias_row = __shfl(bt, n / a.g_q);
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) bias_row[rt] = __shfl(bt, (rt * 32 + n) / a.g_q);
   };
 
-  auto compute = [&](int buf, int kpos0) {
-    const uint16_t* Kb = Ks + buf * C::K_ELEMS;
-    const uint16_t* Vb = Vt + buf * C::V_ELEMS;
-    f32x16 s[2];
+  // One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.  MASKED adds
+  // the causal / sequence-end key mask (diagonal chunk and ragged tail only).
+  auto compute = [&](int buf, int kpos0, auto masked_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const uint16_t* Kb = Ks + buf * C::K_ELEMS + n * C::KLD + h * 8;
+    const uint16_t* Vb = Vt + buf * C::V_ELEMS + n * C::VLD + h * 8;
+    f32x16 s[RT][2];
 #pragma unroll
-    for (int kt = 0; kt < 2; kt++) {
+    for (int rt = 0; rt < RT; rt++)
 #pragma unroll
-      for (int j = 0; j < 16; j++) s[kt][j] = 0.f;
+      for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ks++) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Kb + (kt * 32 + n) * C::KLD + ks * 16 + h * 8);
-        s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], s[kt], 0, 0, 0);
+        for (int j = 0; j < 16; j++) s[rt][kt][j] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++)
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++) {
+        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Kb + kt * 32 * C::KLD + ks * 16);
+#pragma unroll
+        for (int rt = 0; rt < RT; rt++)
+          s[rt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[rt][ks], s[rt][kt], 0, 0, 0);
+      }
+    bf16x8 pb[RT][4];
+    bool grow = false;
+    float tmax[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; rt++) {
+      float mloc = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+          if constexpr (MASKED) {
+            const int kp = kpos0 + kt * 32 + (j >> 2) * 8 + h * 4 + (j & 3);
+            const bool dead = (diag && kp > row_pos[rt]) || kp >= a.n_kv;
+            s[rt][kt][j] = dead ? -INFINITY : s[rt][kt][j];
+          }
+          mloc = fmaxf(mloc, s[rt][kt][j]);
+        }
+      mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+      // max of the base-2 logits s*c1 + bias over the tile (c1 > 0)
+      tmax[rt] = fmaf(mloc, a.c1, bias_row[rt]);
+      grow = grow || (tmax[rt] > m_run[rt] + kLazy);
+    }
+    // Lazy rescaling: the reference max m_run of a row is only raised when the
+    // tile's max exceeds it by more than 2^kLazy; until then p = 2^(t - m_run)
+    // may reach 2^kLazy, which fp32 / bf16 hold without loss, and the final
+    // division by the row sum is unaffected.  Raising it is rare after the
+    // first tiles, so the O rescale below is almost never executed.
+    if (__any(grow)) {
+#pragma unroll
+      for (int rt = 0; rt < RT; rt++) {
+        const float m_new = fmaxf(m_run[rt], tmax[rt]);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float corr = __builtin_amdgcn_exp2f(m_run[rt] - m_use);   // m_run = -inf -> 0
+        m_run[rt] = m_new;
+        l_run[rt] *= corr;
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+          for (int j = 0; j < 16; j++) oacc[rt][dt][j] *= corr;
       }
     }
-    const bool need_mask = diag || (kpos0 + 64 > a.n_kv);
-    float mloc = -INFINITY;
 #pragma unroll
-    for (int kt = 0; kt < 2; kt++)
+    for (int rt = 0; rt < RT; rt++) {
+      const float off = bias_row[rt] - (m_run[rt] == -INFINITY ? 0.f : m_run[rt]);
+      float lsum = 0.f;
 #pragma unroll
-      for (int j = 0; j < 16; j++) {
-        float t = fmaf(s[kt][j], a.c1, bias_row);
-        if (need_mask) {
-          const int kp = kpos0 + kt * 32 + (j >> 2) * 8 + h * 4 + (j & 3);
-          if ((diag && kp > row_pos) || kp >= a.n_kv) t = -INFINITY;
+      for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+          const float pj = __builtin_amdgcn_exp2f(fmaf(s[rt][kt][j], a.c1, off));
+          lsum += pj;
+          pb[rt][kt * 2 + (j >> 3)][j & 7] = (__bf16)pj;
         }
-        s[kt][j] = t;
-        mloc = fmaxf(mloc, t);
-      }
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m_run, mloc);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
-    float lsum = 0.f;
-    bf16x8 pb[4];
-#pragma unroll
-    for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-      for (int j = 0; j < 16; j++) {
-        const float pj = __builtin_amdgcn_exp2f(s[kt][j] - m_use);
-        lsum += pj;
-        pb[kt * 2 + (j >> 3)][j & 7] = (__bf16)pj;
-      }
-    l_run = l_run * corr + lsum;
-    if (__any(corr != 1.f)) {
-#pragma unroll
-      for (int dt = 0; dt < NDT; dt++)
-#pragma unroll
-        for (int j = 0; j < 16; j++) oacc[dt][j] *= corr;
+      l_run[rt] += lsum;
     }
     if constexpr (DECODE) {
       if (wave < D / 32) {
 #pragma unroll
         for (int g = 0; g < 4; g++) {
-          const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vb + (wave * 32 + n) * C::VLD + g * 16 + h * 8);
-          oacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[g], oacc[0], 0, 0, 0);
+          const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vb + wave * 32 * C::VLD + g * 16);
+          oacc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[0][g], oacc[0][0], 0, 0, 0);
         }
       }
     } else {
 #pragma unroll
-      for (int dt = 0; dt < D / 32; dt++)
+      for (int g = 0; g < 4; g++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vb + (dt * 32 + n) * C::VLD + g * 16 + h * 8);
-          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[g], oacc[dt], 0, 0, 0);
+        for (int dt = 0; dt < D / 32; dt++) {
+          const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vb + dt * 32 * C::VLD + g * 16);
+#pragma unroll
+          for (int rt = 0; rt < RT; rt++)
+            oacc[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[rt][g], oacc[rt][dt], 0, 0, 0);
         }
     }
   };
@@ -345,9 +430,15 @@ __global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
   while (have) {
     const int cu = it_u, csub = it_sub;
     const bool more = advance();
-    if (more) stage_load(it_u, it_sub);
+    // bias bookkeeping first: its wait on the previously prefetched bias must not
+    // also wait for the tile loads issued next
     if (csub == 0) begin_chunk(cu);
-    if (wave_on) compute(buf, cu * a.block + csub * 64);
+    if (more) stage_load(it_u, it_sub);
+    if (wave_on) {
+      const int kpos0 = cu * a.block + csub * 64;
+      if (diag || kpos0 + 64 > a.n_kv) compute(buf, kpos0, std::true_type{});
+      else compute(buf, kpos0, std::false_type{});
+    }
     if (more) stage_store(buf ^ 1);
     __syncthreads();
     buf ^= 1;
@@ -355,39 +446,40 @@ __global__ __launch_bounds__(256) void s2_attend_kernel(S2Args a) {
   }
 
   // ---- finalise ------------------------------------------------------------
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-  if constexpr (DECODE) {
-    // partial record per (batch, kv-head, split, head-in-group): D floats of
-    // unnormalised O, then the running max (base-2 logits) and the running sum
-    if (row_ok && wave < D / 32) {
-      float* pp = a.part + ((((int64_t)b * a.h_kv + r) * a.n_tiles + tile) * a.g_q + n) * (D + 2);
 #pragma unroll
-      for (int j = 0; j < 16; j++)
-        pp[wave * 32 + (j >> 2) * 8 + h * 4 + (j & 3)] = oacc[0][j];
-      if (wave == 0 && h == 0) { pp[D] = m_run; pp[D + 1] = l_tot; }
-    }
-    return;
-  }
-  if (row_ok) {
-    uint16_t* op = a.o + b * a.os_b + my_head * a.os_h + (int64_t)my_tok * a.os_t;
+  for (int rt = 0; rt < RT; rt++) {
+    const float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 32);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    if constexpr (DECODE) {
+      // partial record per (batch, kv-head, split, head-in-group): D floats of
+      // unnormalised O, then the running max (base-2 logits) and the running sum
+      if (row_ok[0] && wave < D / 32) {
+        float* pp = a.part + ((((int64_t)b * a.h_kv + r) * a.n_tiles + tile) * a.g_q + n) * (D + 2);
 #pragma unroll
-    for (int dt = 0; dt < NDT; dt++)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        const int d0 = dt * 32 + q4 * 8 + h * 4;
-        uint2 w;
-        w.x = pack_bf16x2(oacc[dt][q4 * 4 + 0] * inv, oacc[dt][q4 * 4 + 1] * inv);
-        w.y = pack_bf16x2(oacc[dt][q4 * 4 + 2] * inv, oacc[dt][q4 * 4 + 3] * inv);
-        *reinterpret_cast<uint2*>(op + d0) = w;
+        for (int j = 0; j < 16; j++)
+          pp[wave * 32 + (j >> 2) * 8 + h * 4 + (j & 3)] = oacc[0][0][j];
+        if (wave == 0 && h == 0) { pp[D] = m_run[0]; pp[D + 1] = l_tot; }
       }
+    } else if (row_ok[rt]) {
+      uint16_t* op = a.o + b * a.os_b + my_head[rt] * a.os_h + (int64_t)my_tok[rt] * a.os_t;
+#pragma unroll
+      for (int dt = 0; dt < NDT; dt++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          const int d0 = dt * 32 + q4 * 8 + h * 4;
+          uint2 w;
+          w.x = pack_bf16x2(oacc[rt][dt][q4 * 4 + 0] * inv, oacc[rt][dt][q4 * 4 + 1] * inv);
+          w.y = pack_bf16x2(oacc[rt][dt][q4 * 4 + 2] * inv, oacc[rt][dt][q4 * 4 + 3] * inv);
+          *reinterpret_cast<uint2*>(op + d0) = w;
+        }
+    }
   }
 }
 
-template <int D, bool DENSE, bool DECODE>
+template <int D, int RT, bool DENSE, bool DECODE>
 static hipError_t launch_s2_t(const S2Args& a, hipStream_t st) {
   using C = S2Cfg<D>;
-  auto kern = s2_attend_kernel<D, DENSE, DECODE>;
+  auto kern = s2_attend_kernel<D, RT, DENSE, DECODE>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -397,6 +489,22 @@ static hipError_t launch_s2_t(const S2Args& a, hipStream_t st) {
   }
   hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), C::LDS_BYTES, st, a);
   return hipGetLastError();
+}
+
+// Row tiles per wave; DASH_S2_ROW_TILES / DASH_DENSE_ROW_TILES = 1|2 override (tuning aids).
+static int env_row_tiles(const char* name, int dflt) {
+  const char* e = getenv(name);
+  if (e && e[0] == '1') return 1;
+  if (e && e[0] == '2') return 2;
+  return dflt;
+}
+static int s2_sparse_row_tiles() {
+  static int v = env_row_tiles("DASH_S2_ROW_TILES", 1);
+  return v;
+}
+static int s2_dense_row_tiles() {
+  static int v = env_row_tiles("DASH_DENSE_ROW_TILES", 2);
+  return v;
 }
 
 static void fill_args(S2Args& a, const dash_params& p, const Layout& L, const void* q, const void* k,
@@ -419,11 +527,17 @@ hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, 
                           bool dense, hipStream_t st) {
   S2Args a;
   fill_args(a, p, L, q, k, v, o, mask, bias);
-  const int tok_tile = 4 * (32 / L.g_q);
+  // rows per wave: 64 for the dense kernel (fewest LDS bytes per flop); the
+  // sparse kernel keeps 32-row waves so that a wave's granule stays small
+  const int rt = dense ? s2_dense_row_tiles() : s2_sparse_row_tiles();
+  const int tok_tile = 4 * (32 * rt / L.g_q);
   a.n_tiles = (p.n_q + tok_tile - 1) / tok_tile;
-  if (p.head_dim == 128)
-    return dense ? launch_s2_t<128, true, false>(a, st) : launch_s2_t<128, false, false>(a, st);
-  return dense ? launch_s2_t<64, true, false>(a, st) : launch_s2_t<64, false, false>(a, st);
+#define DASH_S2(D_)                                                                              \
+  (rt == 2 ? (dense ? launch_s2_t<D_, 2, true, false>(a, st) : launch_s2_t<D_, 2, false, false>(a, st)) \
+           : (dense ? launch_s2_t<D_, 1, true, false>(a, st) : launch_s2_t<D_, 1, false, false>(a, st)))
+  if (p.head_dim == 128) return DASH_S2(128);
+  return DASH_S2(64);
+#undef DASH_S2
 }
 
 // Merge of the split-KV partials: o = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
@@ -459,9 +573,9 @@ hipError_t launch_decode_s2(const dash_params& p, const Layout& L, const void* q
   a.part = partials;
   hipError_t e;
   if (p.head_dim == 128)
-    e = dense ? launch_s2_t<128, true, true>(a, st) : launch_s2_t<128, false, true>(a, st);
+    e = dense ? launch_s2_t<128, 1, true, true>(a, st) : launch_s2_t<128, 1, false, true>(a, st);
   else
-    e = dense ? launch_s2_t<64, true, true>(a, st) : launch_s2_t<64, false, true>(a, st);
+    e = dense ? launch_s2_t<64, 1, true, true>(a, st) : launch_s2_t<64, 1, false, true>(a, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(decode_merge_kernel<uint16_t>, dim3(p.h_q, p.batch), dim3(128), 0, st, partials,
                      (uint16_t*)o, p.h_q, p.h_kv, L.g_q, L.splits, p.head_dim, p.o_stride[0],
