@@ -45,6 +45,8 @@ template <> struct elem<uint16_t> {
 template <int CTRL> __device__ __forceinline__ float dpp_f(float v) {
   return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
 }
+struct OpAdd { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
+struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
 // combine over the 16 lanes of a DPP row; every lane of the row gets the result
 template <typename Op> __device__ __forceinline__ float row16_reduce(float v, Op op) {
   v = op(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
@@ -53,24 +55,24 @@ template <typename Op> __device__ __forceinline__ float row16_reduce(float v, Op
   v = op(v, dpp_f<0x140>(v));  // row_mirror
   return v;
 }
+// Whole-wave combine: DPP inside each 16-lane row, then the four row results are
+// read as scalars (no LDS round trip).  The result is wave-uniform by
+// construction, so every decision derived from it is identical in all lanes.
 template <typename Op> __device__ __forceinline__ float wave_reduce(float v, Op op) {
   v = row16_reduce(v, op);
-  v = op(v, __shfl_xor(v, 16));
-  v = op(v, __shfl_xor(v, 32));
-  return v;
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return op(op(r0, r1), op(r2, r3));
 }
-struct OpAdd { __device__ __forceinline__ float operator()(float a, float b) const { return a + b; } };
-struct OpMax { __device__ __forceinline__ float operator()(float a, float b) const { return fmaxf(a, b); } };
-// Wave-wide results are taken from lane 0 and broadcast as a scalar: the compiler
-// may contract a multiply feeding the first reduction step into an FMA, which
-// makes the butterfly's partial sums differ by an ulp from lane to lane.  Any
-// decision derived from the result must be identical in all lanes.
 __device__ __forceinline__ float wave_sum(float v) {
-  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(wave_reduce(v, OpAdd()))));
+  // materialise v first: a multiply contracted into the first DPP add would make
+  // lane 0 of each row see a differently rounded partial sum than its partner
+  asm volatile("" : "+v"(v));
+  return wave_reduce(v, OpAdd());
 }
-__device__ __forceinline__ float wave_max(float v) {
-  return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(wave_reduce(v, OpMax()))));
-}
+__device__ __forceinline__ float wave_max(float v) { return wave_reduce(v, OpMax()); }
 __device__ __forceinline__ float row16_sum(float v) { return row16_reduce(v, OpAdd()); }
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }

@@ -149,6 +149,109 @@ __device__ __forceinline__ void solve_wave_rows(float* S, const S1Args& a, int r
   }
 }
 
+// Same solve with one row per 16-lane DPP row: a wave works on four rows at once
+// (rows row0 + 4q for DPP row q, which keeps the LDS reads conflict-free), lane
+// l of a DPP row holds chunks l, l+16, ...  All per-row quantities are per-lane
+// values that are equal inside a DPP row, the reductions stay inside the row (no
+// LDS round trip), and finished rows simply stop updating.  Used while a row
+// fits 32 registers per lane (n_cand <= 512).
+template <int NJ, int MODE>
+__device__ __forceinline__ void solve_rows16(float* S, int ld, int row0, int n_cand, float alpha,
+                                             float p, int lane, float& tau_out) {
+  const int l16 = lane & 15, row = row0 + 4 * (lane >> 4);
+  float v[NJ];
+  float m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int c = l16 + 16 * j;
+    v[j] = c < n_cand ? S[row * ld + c] : -INFINITY;
+    m = fmaxf(m, v[j]);
+  }
+  const float mx = row16_reduce(m, OpMax());
+  float lo = mx - 1.f;
+  float hi = mx - exp2f(-(alpha - 1.f) * log2f((float)n_cand));
+  float tau = lo;
+  if constexpr (MODE != MODE_BISECT) {
+    // Warm start: the root of the same equation restricted to the 16 lane maxima
+    // is a lower bound of tau (dropping terms lowers the residual), and so is
+    // every Newton iterate from the left on it.  A few cheap steps on one value
+    // per lane land close to tau; the bracket below still covers any overshoot.
+#pragma unroll
+    for (int it = 0; it < 5; it++) {
+      float f, g;
+      pow_terms<MODE>(fmaxf(m - tau, 0.f), p, f, g);
+      asm volatile("" : "+v"(f), "+v"(g));
+      const float F = row16_reduce(f, OpAdd()), G = row16_reduce(g, OpAdd());
+      if (F > 1.f && G > 0.f) tau += (F - 1.f) / (p * G);
+    }
+    tau = fmaxf(tau, lo);
+    if (!(tau < hi)) tau = lo;
+  }
+  bool done = false;
+  for (int it = 0; it < 64; it++) {
+    float F = 0.f, G = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; j++) {
+      float f, g;
+      pow_terms<MODE>(fmaxf(v[j] - tau, 0.f), p, f, g);
+      F += f; G += g;
+    }
+    // keep the partial sums as rounded values: a multiply contracted into the
+    // first cross-lane add would make the lanes of a row disagree by an ulp
+    asm volatile("" : "+v"(F), "+v"(G));
+    F = row16_reduce(F, OpAdd());
+    G = row16_reduce(G, OpAdd());
+    if (!done) {
+      const float f = F - 1.f;
+      if (f == 0.f) {
+        done = true;
+      } else {
+        if (f > 0.f) lo = tau; else hi = tau;
+        const float mid = 0.5f * (lo + hi);
+        float cand = (MODE == MODE_BISECT || !(G > 0.f)) ? mid : tau + f / (p * G);
+        if (MODE != MODE_BISECT && cand == tau) {
+          done = true;
+        } else {
+          if (!(cand > lo && cand < hi)) cand = mid;
+          if (!(cand > lo && cand < hi)) { done = true; tau = lo; }
+          else {
+            // alpha = 1.5: a Newton step s from the left leaves an error of about
+            // (k / 2G) s^2 <= (n / 2G) s^2 (f'' = 2k, f' = -2G); once that is below
+            // 2e-8 the step is final and the confirming evaluation is skipped
+            if (MODE == MODE_P2 && f > 0.f && cand != mid) {
+              const float st = cand - tau;
+              if ((float)n_cand * st * st < 4e-8f * G) done = true;
+            }
+            tau = cand;
+          }
+        }
+      }
+    }
+    if (!__any(!done)) break;
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; j++) {
+    const int c = l16 + 16 * j;
+    if (c < n_cand) S[row * ld + c] = pow_p<MODE>(fmaxf(v[j] - tau, 0.f), p);
+  }
+  tau_out = tau;
+}
+
+template <int NJ, int MODE>
+__device__ __forceinline__ void solve_wave_rows16(float* S, const S1Args& a, int wave, int passes,
+                                                  int n_cand, int lane, int b, int r, int tok0) {
+  for (int ps = 0; ps < passes; ps++) {
+    const int row0 = ps * 16 + wave;
+    float t;
+    solve_rows16<NJ, MODE>(S, a.ld, row0, n_cand, a.alpha, a.pexp, lane, t);
+    if (a.tau && (lane & 15) == 0) {
+      const int row = row0 + 4 * (lane >> 4);
+      const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
+      if (tok < a.n_q) a.tau[((int64_t)b * a.h_q + head) * a.n_q + tok] = t;
+    }
+  }
+}
+
 template <int NJ>
 __device__ __forceinline__ void emit_token(const float* S, const S1Args& a, uint32_t* mw, int tl,
                                            int tok, int n_cand, int lane, int b, int r) {
@@ -162,7 +265,8 @@ __device__ __forceinline__ void emit_token(const float* S, const S1Args& a, uint
     if (c < n_cand)
       for (int h = 0; h < a.g_q; h++) s += S[(tl * a.g_q + h) * a.ld + c];
     s *= inv_g;
-    lw[j] = s > 0.f ? logf(s) : INFINITY;   // +inf marks "not routed"
+    // ln via the hardware log2 (about 1 ulp): ample for a bias that is divided by sigma
+    lw[j] = s > 0.f ? __builtin_amdgcn_logf(s) * 0.6931471805599453f : INFINITY;   // +inf marks "not routed"
     if (s > 0.f) { slog += lw[j]; nsup += 1.f; }
   }
   slog = wave_sum(slog);
@@ -233,31 +337,47 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
           qf[mt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 32);
       }
       const int ntile_c = (n_cand + 15) >> 4;
-      for (int ct = wave; ct < ntile_c; ct += 4) {
+      const uint16_t* kb = a.ksplit + ((int64_t)b * a.h_kv + r) * a.t_c * 3 * D + kq * 8;
+      // operand registers are double buffered: the loads of this wave's next chunk
+      // tile are in flight while the current one goes through the MFMAs
+      bf16x8 kf[2][3][D / 32];
+      auto load_tile = [&](int ct, bf16x8 (&dst)[3][D / 32]) {
         const int c = ct * 16 + m;
-        const int cl = c < n_cand ? c : n_cand - 1;
-        const uint16_t* kp = a.ksplit + (((int64_t)b * a.h_kv + r) * a.t_c + cl) * 3 * D + kq * 8;
+        const uint16_t* kp = kb + (int64_t)(c < n_cand ? c : n_cand - 1) * 3 * D;
+#pragma unroll
+        for (int sp = 0; sp < 3; sp++)
+#pragma unroll
+          for (int ks = 0; ks < D / 32; ks++)
+            dst[sp][ks] = *reinterpret_cast<const bf16x8*>(kp + sp * D + ks * 32);
+      };
+      auto mma_tile = [&](int ct, const bf16x8 (&src)[3][D / 32]) {
         f32x4 acc_hi[MT], acc_lo[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) { acc_hi[mt] = f32x4{0, 0, 0, 0}; acc_lo[mt] = f32x4{0, 0, 0, 0}; }
 #pragma unroll
-        for (int ks = 0; ks < D / 32; ks++) {
-          const bf16x8 k0 = *reinterpret_cast<const bf16x8*>(kp + ks * 32);
-          const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(kp + D + ks * 32);
-          const bf16x8 k2 = *reinterpret_cast<const bf16x8*>(kp + 2 * D + ks * 32);
+        for (int ks = 0; ks < D / 32; ks++)
 #pragma unroll
           for (int mt = 0; mt < MT; mt++) {
-            acc_hi[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], k0, acc_hi[mt], 0, 0, 0);
-            acc_lo[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], k1, acc_lo[mt], 0, 0, 0);
-            acc_lo[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], k2, acc_lo[mt], 0, 0, 0);
+            acc_hi[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], src[0][ks], acc_hi[mt], 0, 0, 0);
+            acc_lo[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], src[1][ks], acc_lo[mt], 0, 0, 0);
+            acc_lo[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[mt][ks], src[2][ks], acc_lo[mt], 0, 0, 0);
           }
-        }
+        const int c = ct * 16 + m;
         if (c < n_cand) {
 #pragma unroll
           for (int mt = 0; mt < MT; mt++)
 #pragma unroll
             for (int j = 0; j < 4; j++)
               S[(mt * 16 + 4 * kq + j) * a.ld + c] = (acc_hi[mt][j] + acc_lo[mt][j]) * a.xscale;
+        }
+      };
+      if (wave < ntile_c) load_tile(wave, kf[0]);
+      for (int ct = wave; ct < ntile_c; ct += 8) {
+        if (ct + 4 < ntile_c) load_tile(ct + 4, kf[1]);
+        mma_tile(ct, kf[0]);
+        if (ct + 4 < ntile_c) {
+          if (ct + 8 < ntile_c) load_tile(ct + 8, kf[0]);
+          mma_tile(ct + 4, kf[1]);
         }
       }
     } else {
@@ -288,12 +408,21 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
     case MODE_GEN: solve_wave_rows<NJ_, MODE_GEN>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
     default: solve_wave_rows<NJ_, MODE_BISECT>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
   }
-    if (nj <= 1) { DASH_SOLVE(1) }
-    else if (nj <= 2) { DASH_SOLVE(2) }
-    else if (nj <= 4) { DASH_SOLVE(4) }
-    else if (nj <= 8) { DASH_SOLVE(8) }
+#define DASH_SOLVE16(NJ_)                                                                        \
+  switch (mode) {                                                                                \
+    case MODE_P1: solve_wave_rows16<NJ_, MODE_P1>(S, a, wave, MT, n_cand, lane, b, r, tok0); break; \
+    case MODE_P2: solve_wave_rows16<NJ_, MODE_P2>(S, a, wave, MT, n_cand, lane, b, r, tok0); break; \
+    case MODE_P4: solve_wave_rows16<NJ_, MODE_P4>(S, a, wave, MT, n_cand, lane, b, r, tok0); break; \
+    case MODE_GEN: solve_wave_rows16<NJ_, MODE_GEN>(S, a, wave, MT, n_cand, lane, b, r, tok0); break; \
+    default: solve_wave_rows16<NJ_, MODE_BISECT>(S, a, wave, MT, n_cand, lane, b, r, tok0); break; \
+  }
+    if (n_cand <= 64) { DASH_SOLVE16(4) }
+    else if (n_cand <= 128) { DASH_SOLVE16(8) }
+    else if (n_cand <= 256) { DASH_SOLVE16(16) }
+    else if (n_cand <= 512) { DASH_SOLVE16(32) }
     else if (nj <= 16) { DASH_SOLVE(16) }
     else { DASH_SOLVE(32) }
+#undef DASH_SOLVE16
 #undef DASH_SOLVE
   } else if (a.tau) {
     for (int row = threadIdx.x; row < ROWS; row += 256) {
