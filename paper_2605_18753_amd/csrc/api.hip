@@ -1,6 +1,7 @@
 // C ABI of the DashAttention library: argument validation, workspace carving and
 // kernel sequencing.  Host code only; every kernel lives in its own file.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "dash_internal.h"
@@ -50,7 +51,9 @@ int make_layout(const dash_params* p, Layout* L, bool routing) {
   int splits = 1;
   if (decode_mfma) {
     const int pairs = p->batch * p->h_kv;
-    splits = (1024 + pairs - 1) / pairs;
+    const char* env = getenv("DASH_DECODE_WGS");   // tuning aid: target workgroup count
+    const int target = env ? atoi(env) : 512;
+    splits = (target + pairs - 1) / pairs;
     if (splits > 32) splits = 32;
     if (splits > L->t_all) splits = L->t_all;
     if (splits < 1) splits = 1;

@@ -73,7 +73,7 @@ __device__ __forceinline__ void solve_rows(float* S, int ld, int row0, int n_can
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
       const int c = lane + 64 * j;
-      v[rb][j] = c < n_cand ? S[(row0 + rb) * ld + c] : -INFINITY;
+      v[rb][j] = c < n_cand ? S[(row0 + 4 * rb) * ld + c] : -INFINITY;
       m = fmaxf(m, v[rb][j]);
     }
     mx[rb] = wave_max(m);
@@ -81,6 +81,24 @@ __device__ __forceinline__ void solve_rows(float* S, int ld, int row0, int n_can
     hi[rb] = mx[rb] - exp2f(-(alpha - 1.f) * log2f((float)n_cand));
     tau[rb] = lo[rb];
     done[rb] = false;
+  }
+  if constexpr (MODE != MODE_BISECT) {
+    // warm start on the 64 lane maxima (a subset: its root and every Newton
+    // iterate from the left on it are lower bounds of tau)
+#pragma unroll
+    for (int rb = 0; rb < RB; rb++) {
+      float ml = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < NJ; j++) ml = fmaxf(ml, v[rb][j]);
+      for (int it = 0; it < 5; it++) {
+        float f, g;
+        pow_terms<MODE>(fmaxf(ml - tau[rb], 0.f), p, f, g);
+        const float F = wave_sum(f), G = wave_sum(g);
+        if (F > 1.f && G > 0.f) tau[rb] += (F - 1.f) / (p * G);
+      }
+      tau[rb] = fmaxf(tau[rb], lo[rb]);
+      if (!(tau[rb] < hi[rb])) tau[rb] = lo[rb];
+    }
   }
   for (int it = 0; it < 64; it++) {
     bool all_done = true;
@@ -111,6 +129,10 @@ __device__ __forceinline__ void solve_rows(float* S, int ld, int row0, int n_can
               done[rb] = true;                     // bracket closed: adjacent floats
               tau[rb] = lo[rb];
             } else {
+              if (MODE == MODE_P2 && f > 0.f && cand != mid) {   // see solve_rows16
+                const float st = cand - tau[rb];
+                if ((float)n_cand * st * st < 4e-8f * G) done[rb] = true;
+              }
               tau[rb] = cand;
             }
           }
@@ -125,25 +147,29 @@ __device__ __forceinline__ void solve_rows(float* S, int ld, int row0, int n_can
 #pragma unroll
     for (int j = 0; j < NJ; j++) {
       const int c = lane + 64 * j;
-      if (c < n_cand) S[(row0 + rb) * ld + c] = pow_p<MODE>(fmaxf(v[rb][j] - tau[rb], 0.f), p);
+      if (c < n_cand) S[(row0 + 4 * rb) * ld + c] = pow_p<MODE>(fmaxf(v[rb][j] - tau[rb], 0.f), p);
     }
     tau_out[rb] = tau[rb];
   }
 }
 
+// Rows are dealt to the four waves round robin (wave w: rows w, w+4, ...), so a
+// decode tile with only g_q valid rows still uses all waves; rows of tokens past
+// the end of the sequence are skipped.
 template <int NJ, int MODE>
-__device__ __forceinline__ void solve_wave_rows(float* S, const S1Args& a, int row_begin, int nrows,
+__device__ __forceinline__ void solve_wave_rows(float* S, const S1Args& a, int wave, int nrows,
                                                 int n_cand, int lane, int b, int r, int tok0) {
   constexpr int RB = NJ <= 8 ? 4 : (NJ == 16 ? 2 : 1);
-  for (int rr = 0; rr < nrows; rr += RB) {
+  for (int rr = wave; rr < nrows; rr += 4 * RB) {
+    if (tok0 + rr / a.g_q >= a.n_q) break;      // this and all later rows are padding
     float t[RB];
-    solve_rows<NJ, RB, MODE>(S, a.ld, row_begin + rr, n_cand, a.alpha, a.pexp, lane, t);
+    solve_rows<NJ, RB, MODE>(S, a.ld, rr, n_cand, a.alpha, a.pexp, lane, t);
     if (a.tau && lane == 0) {
 #pragma unroll
       for (int rb = 0; rb < RB; rb++) {
-        const int row = row_begin + rr + rb;
+        const int row = rr + 4 * rb;
         const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
-        if (tok < a.n_q) a.tau[((int64_t)b * a.h_q + head) * a.n_q + tok] = t[rb];
+        if (row < nrows && tok < a.n_q) a.tau[((int64_t)b * a.h_q + head) * a.n_q + tok] = t[rb];
       }
     }
   }
@@ -393,7 +419,6 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
 
   const int nj = (n_cand + 63) >> 6;
   if (n_cand > 0) {
-    const int rpw = ROWS / 4, row_begin = wave * rpw;
     int mode;
     if (a.pexp < 1.f) mode = MODE_BISECT;
     else if (a.pexp == 1.f) mode = MODE_P1;
@@ -402,11 +427,11 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
     else mode = MODE_GEN;
 #define DASH_SOLVE(NJ_)                                                                          \
   switch (mode) {                                                                                \
-    case MODE_P1: solve_wave_rows<NJ_, MODE_P1>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
-    case MODE_P2: solve_wave_rows<NJ_, MODE_P2>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
-    case MODE_P4: solve_wave_rows<NJ_, MODE_P4>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
-    case MODE_GEN: solve_wave_rows<NJ_, MODE_GEN>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
-    default: solve_wave_rows<NJ_, MODE_BISECT>(S, a, row_begin, rpw, n_cand, lane, b, r, tok0); break; \
+    case MODE_P1: solve_wave_rows<NJ_, MODE_P1>(S, a, wave, ROWS, n_cand, lane, b, r, tok0); break; \
+    case MODE_P2: solve_wave_rows<NJ_, MODE_P2>(S, a, wave, ROWS, n_cand, lane, b, r, tok0); break; \
+    case MODE_P4: solve_wave_rows<NJ_, MODE_P4>(S, a, wave, ROWS, n_cand, lane, b, r, tok0); break; \
+    case MODE_GEN: solve_wave_rows<NJ_, MODE_GEN>(S, a, wave, ROWS, n_cand, lane, b, r, tok0); break; \
+    default: solve_wave_rows<NJ_, MODE_BISECT>(S, a, wave, ROWS, n_cand, lane, b, r, tok0); break; \
   }
 #define DASH_SOLVE16(NJ_)                                                                        \
   switch (mode) {                                                                                \
@@ -446,45 +471,61 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
 }
 
 // fp32 scores for fp32 inputs and for decode: one 16-lane DPP row per chunk,
-// coalesced float4 reads of the fp32 summaries, fp32 FMA, row reduction.
+// coalesced float4 reads of the fp32 summaries, fp32 FMA, row reduction.  A
+// workgroup covers 64 chunks (four per DPP row) and issues all its summary loads
+// before the first use, so enough bytes are in flight to stream the cache.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void s1_scores_f32_kernel(
     const T* __restrict__ q, const float* __restrict__ kbar, float* __restrict__ scores, int h_q,
     int h_kv, int g_q, int n_q, int block, int t_c, int pos0, int causal, int64_t qs_b,
     int64_t qs_h, int64_t qs_t, float xscale) {
+  constexpr int CPG = 4;                      // chunks per 16-lane group
   const int tok = blockIdx.y;
   const int b = blockIdx.z / h_kv, r = blockIdx.z % h_kv;
   int n_cand = causal ? (pos0 + tok) / block : t_c;
   if (n_cand > t_c) n_cand = t_c;
-  const int c0 = blockIdx.x * 16;
+  const int c0 = blockIdx.x * 16 * CPG;
   if (c0 >= n_cand) return;
   const int cl = threadIdx.x >> 4, l16 = threadIdx.x & 15;
-  const int c = c0 + cl;
-  const float* kp = kbar + (((int64_t)b * h_kv + r) * t_c + (c < n_cand ? c : n_cand - 1)) * D + 4 * l16;
-  float kk[D / 64][4];
+  const float* kbase = kbar + ((int64_t)b * h_kv + r) * t_c * D + 4 * l16;
+  float kk[CPG][D / 64][4];
 #pragma unroll
-  for (int i = 0; i < D / 64; i++) {
-    const f32x4 t = *reinterpret_cast<const f32x4*>(kp + 64 * i);
-    kk[i][0] = t[0]; kk[i][1] = t[1]; kk[i][2] = t[2]; kk[i][3] = t[3];
+  for (int u = 0; u < CPG; u++) {
+    const int c = c0 + u * 16 + cl;
+    const float* kp = kbase + (int64_t)(c < n_cand ? c : n_cand - 1) * D;
+#pragma unroll
+    for (int i = 0; i < D / 64; i++) {
+      const f32x4 t = *reinterpret_cast<const f32x4*>(kp + 64 * i);
+      kk[u][i][0] = t[0]; kk[u][i][1] = t[1]; kk[u][i][2] = t[2]; kk[u][i][3] = t[3];
+    }
   }
   for (int h = 0; h < g_q; h++) {
     const int head = r * g_q + h;
     const T* qp = q + b * qs_b + head * qs_h + (int64_t)tok * qs_t + 4 * l16;
-    float acc = 0.f;
+    float qv[D / 64][4];
 #pragma unroll
     for (int i = 0; i < D / 64; i++)
 #pragma unroll
-      for (int e = 0; e < 4; e++) acc = fmaf(elem<T>::ld(qp + 64 * i + e), kk[i][e], acc);
-    acc = row16_sum(acc);
-    if (l16 == 0 && c < n_cand)
-      scores[(((int64_t)b * h_q + head) * n_q + tok) * t_c + c] = acc * xscale;
+      for (int e = 0; e < 4; e++) qv[i][e] = elem<T>::ld(qp + 64 * i + e);
+    float* srow = scores + (((int64_t)b * h_q + head) * n_q + tok) * t_c;
+#pragma unroll
+    for (int u = 0; u < CPG; u++) {
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < D / 64; i++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) acc = fmaf(qv[i][e], kk[u][i][e], acc);
+      acc = row16_sum(acc);
+      const int c = c0 + u * 16 + cl;
+      if (l16 == 0 && c < n_cand) srow[c] = acc * xscale;
+    }
   }
 }
 
 hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const void* q,
                                 const float* kbar, float* scores, hipStream_t st) {
   if (L.t_c == 0) return hipSuccess;
-  dim3 grid((L.t_c + 15) / 16, p.n_q, p.batch * p.h_kv), blk(256);
+  dim3 grid((L.t_c + 63) / 64, p.n_q, p.batch * p.h_kv), blk(256);
 #define DASH_SC(T_, D_)                                                                           \
   hipLaunchKernelGGL((s1_scores_f32_kernel<T_, D_>), grid, blk, 0, st, (const T_*)q, kbar, scores, \
                      p.h_q, p.h_kv, L.g_q, p.n_q, p.block_size, L.t_c, L.pos0, p.causal,          \

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
     for (int i = tid; i < 64; i += 256) { const uint32_t w = wgmask[i]; wvmask[i] = w; wvmask[64 + i] = w; wvmask[128 + i] = w; wvmask[192 + i] = w; }
     __syncthreads();
   }
-  if (!DENSE && trk_ok && trk_rank < a.t_all) trk_next = trk_bias[trk_rank];
+  if (!DENSE && !DECODE && trk_ok && trk_rank < a.t_all) trk_next = trk_bias[trk_rank];
 
   // ---- tile iterator (workgroup-uniform) ---------------------------------
   int it_wi = -1, it_sub = nsub - 1, it_u = -1;
@@ -217,6 +217,7 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
   const char* kbase = reinterpret_cast<const char*>(a.k + b * a.ks_b + r * a.ks_h);
   const char* vbase = reinterpret_cast<const char*>(a.v + b * a.vs_b + r * a.vs_h);
   u32x4 sreg[8];
+  u32x4 sreg2[DECODE ? 8 : 1];   // decode: second set, tiles are fetched two ahead
   const int v_sg = st & 7, v_dg = st >> 3;          // V: slot group, 8-column group
   constexpr int KROWS = 128 / (D / 8);              // K rows covered by one load of the 128 threads
   const int k_row0 = st / (D / 8), k_col = (st % (D / 8)) * 8;
@@ -224,7 +225,7 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
   const uint32_t k_toff = (uint32_t)(k_row0 * a.ks_t + k_col) * 2u;     // bytes
   const uint32_t v_toff = (uint32_t)(v_row0 * a.vs_t + v_dg * 8) * 2u;
   const bool v_active = v_dg < D / 8;
-  auto stage_load = [&](int u, int sub) {
+  auto stage_load = [&](int u, int sub, u32x4 (&sreg)[8]) {
     const int kpos0 = u * a.block + sub * 64;
     if (kpos0 + 64 <= a.n_kv) {
       if (stage_k) {
@@ -259,7 +260,7 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
   };
   uint16_t* const k_dst0 = Ks + k_row0 * C::KLD + k_col;
   uint16_t* const v_dst0 = Vt + (v_dg * 8) * C::VLD + v_sg * 8;
-  auto stage_store = [&](int buf) {
+  auto stage_store = [&](int buf, const u32x4 (&sreg)[8]) {
     if (stage_k) {
       uint16_t* dst = k_dst0 + buf * C::K_ELEMS;
 #pragma unroll
@@ -300,11 +301,24 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
   for (int rt = 0; rt < RT; rt++) bias_row[rt] = 0.f;
   bool wave_on = false, diag = false;
 
+  // DECODE: one token per workgroup, so the bias list is walked with wave-uniform
+  // (scalar) loads; they do not queue behind the vector loads of the tile prefetch.
+  const float* dec_bias = DENSE ? nullptr : a.bias + (((int64_t)b * a.h_kv + r) * a.n_q) * a.t_all;
+  int dec_rank = DECODE ? __builtin_amdgcn_readfirstlane(trk_rank) : 0;
+
   auto begin_chunk = [&](int u) {
     // decides participation and fetches the per-token bias of chunk u
     wave_on = wave_ok && ((__builtin_amdgcn_readfirstlane(wvmask[wave * 64 + (u >> 5)]) >> (u & 31)) & 1u);
     diag = a.causal && u == cw;
     if (!wave_on) return;
+    if constexpr (DECODE) {
+      // every chunk this workgroup visits is one of the token's attended chunks,
+      // in list order; padded rows simply share the bias
+      float bt = 0.f;
+      if (!DENSE && !diag) { bt = dec_bias[dec_rank] * kLog2e; dec_rank++; }
+      bias_row[0] = bt;
+      return;
+    }
     float bt = 0.f;
     if (!DENSE && !diag) {
       bt = -INFINITY;
@@ -420,29 +434,67 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
   };
 
   // ---- main loop -----------------------------------------------------------
-  bool have = advance();
-  int buf = 0;
-  if (have) {
-    stage_load(it_u, it_sub);
-    stage_store(0);
-  }
-  __syncthreads();
-  while (have) {
-    const int cu = it_u, csub = it_sub;
-    const bool more = advance();
-    // bias bookkeeping first: its wait on the previously prefetched bias must not
-    // also wait for the tile loads issued next
-    if (csub == 0) begin_chunk(cu);
-    if (more) stage_load(it_u, it_sub);
+  auto run_tile = [&](int cu, int csub, int buf) {
     if (wave_on) {
       const int kpos0 = cu * a.block + csub * 64;
       if (diag || kpos0 + 64 > a.n_kv) compute(buf, kpos0, std::true_type{});
       else compute(buf, kpos0, std::false_type{});
     }
-    if (more) stage_store(buf ^ 1);
+  };
+  int buf = 0;
+  if constexpr (!DECODE) {
+    bool have = advance();
+    if (have) {
+      stage_load(it_u, it_sub, sreg);
+      stage_store(0, sreg);
+    }
     __syncthreads();
-    buf ^= 1;
-    have = more;
+    while (have) {
+      const int cu = it_u, csub = it_sub;
+      const bool more = advance();
+      // bias bookkeeping first: its wait on the previously prefetched bias must not
+      // also wait for the tile loads issued next
+      if (csub == 0) begin_chunk(cu);
+      if (more) stage_load(it_u, it_sub, sreg);
+      run_tile(cu, csub, buf);
+      if (more) stage_store(buf ^ 1, sreg);
+      __syncthreads();
+      buf ^= 1;
+      have = more;
+    }
+  } else {
+    // Decode is bound by HBM latency x bandwidth, not by compute: keep two tiles
+    // (64 KB per workgroup) in flight.  While tile j is computed from LDS, tile
+    // j+1 and tile j+2 are on their way into the two register sets, which swap
+    // roles every iteration (the loop body is written out twice).
+    bool have0 = advance();
+    int u0 = it_u, s0 = it_sub;
+    if (have0) { stage_load(u0, s0, sreg); stage_store(0, sreg); }
+    bool have1 = have0 && advance();
+    int u1 = it_u, s1 = it_sub;
+    if (have1) stage_load(u1, s1, sreg);
+    bool have2 = have1 && advance();
+    int u2 = it_u, s2 = it_sub;
+    if (have2) stage_load(u2, s2, sreg2);
+    __syncthreads();
+    auto step = [&](u32x4 (&pr)[8]) {
+      // pr holds tile j+1 (if any); after it is stored it receives tile j+3
+      if (s0 == 0) begin_chunk(u0);
+      run_tile(u0, s0, buf);
+      if (have1) stage_store(buf ^ 1, pr);
+      const bool have3 = have2 && advance();
+      if (have3) stage_load(it_u, it_sub, pr);
+      __syncthreads();
+      buf ^= 1;
+      have0 = have1; u0 = u1; s0 = s1;
+      have1 = have2; u1 = u2; s1 = s2;
+      have2 = have3; u2 = it_u; s2 = it_sub;
+    };
+    while (have0) {
+      step(sreg);
+      if (!have0) break;
+      step(sreg2);
+    }
   }
 
   // ---- finalise ------------------------------------------------------------
