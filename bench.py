@@ -27,6 +27,10 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the Stage-2 kernel on the full C2 workload, from the two
+# rocprofv3 --pmc runs summarised in profiles/bench_c2_c3_hbm_traffic.md
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0).  Not measurable from inside this script.
+S2_TRAFFIC_BYTES_C2 = 2.396e9 + 0.268e9
 
 
 def parse():
@@ -38,6 +42,9 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--small", action="store_true", help="shrunken shapes (debugging)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy three times (known traffic, to scale the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -197,6 +204,14 @@ def main():
         w = w.replace(n_q=4096, n_kv=4096, name="C2_small")
         wd = wd.replace(n_kv=16384, batch=4, name="C3_small")
 
+    if a.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     main_res = bench_prefill(w, a.steps, a.warmup, torch, B, make_inputs)
     # the gamma that lands near 75 % chunk sparsity on this generator
     w75 = w.replace(gamma=1.5)
@@ -221,9 +236,10 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "h_q": w.h_q, "h_kv": w.h_kv, "n": w.n_q,
                    "head_dim": w.head_dim, "block": w.block, "alpha": w.alpha, "gamma": w.gamma,
                    "sigma": w.sigma, "causal": True, "offset_sigma": w.offset_sigma, "seed": w.seed},
-        "roofline": {"bound": "mfma", "kernel": "s2_attend_kernel<128,false,false>",
+        "roofline": {"bound": "mfma", "kernel": "s2_attend_kernel<128,1,false,false>",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None if a.small else S2_TRAFFIC_BYTES_C2},
         "cpu_baseline": cpu,
         "extras": {
             "chunk_sparsity": main_res["sparsity"],

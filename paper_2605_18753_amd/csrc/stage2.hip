@@ -555,7 +555,7 @@ static int s2_sparse_row_tiles() {
   return v;
 }
 static int s2_dense_row_tiles() {
-  static int v = env_row_tiles("DASH_DENSE_ROW_TILES", 2);
+  static int v = env_row_tiles("DASH_DENSE_ROW_TILES", 1);
   return v;
 }
 
@@ -579,8 +579,9 @@ hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, 
                           bool dense, hipStream_t st) {
   S2Args a;
   fill_args(a, p, L, q, k, v, o, mask, bias);
-  // rows per wave: 64 for the dense kernel (fewest LDS bytes per flop); the
-  // sparse kernel keeps 32-row waves so that a wave's granule stays small
+  // 32-row waves by default: they fit 256 VGPRs, so two workgroups share a CU.
+  // The 64-row variant halves the LDS bytes per flop but needs a whole SIMD's
+  // register file per wave; it is kept as a tuning option.
   const int rt = dense ? s2_dense_row_tiles() : s2_sparse_row_tiles();
   const int tok_tile = 4 * (32 * rt / L.g_q);
   a.n_tiles = (p.n_q + tok_tile - 1) / tok_tile;
