@@ -1,27 +1,33 @@
-// Stage 2 (bf16): block-sparse softmax attention over the routed chunks with the
-// Stage-1 bias added to the logits (Sec. 3.3 Eq. 6 in the bias form of
+// Stage 2 (bf16 prefill): block-sparse softmax attention over the routed chunks
+// with the Stage-1 bias added to the logits (Sec. 3.3 Eq. 6 in the bias form of
 // Proposition 1; Alg. 3), and the dense reference attention (Eq. 1) from the
 // same template.
 //
 // Tiling.  A workgroup (4 waves) owns 128 (token, head) rows of one kv-head:
-// wave w owns 32 rows = all g_q heads of 32/g_q consecutive tokens (its
-// "granule").  The workgroup walks the union of its tokens' chunk masks in
-// ascending order; every 64-key tile of K and V is staged once in LDS (double
-// buffered: the global loads of tile j+1 are in flight while tile j is
-// computed) and a wave skips the MFMA work of a chunk none of its tokens kept.
-// Rows of a granule that did not keep a chunk get bias -inf for it, which keeps
-// the per-token result exact.
+// wave w owns 32 rows = all g_q heads of 32/g_q consecutive tokens.  The
+// workgroup walks the union of its tokens' chunk masks in ascending order.
+// Every 64-key tile of K and V is copied once from global memory straight into
+// LDS (global_load_lds_dwordx4, no staging registers), two stages deep: the copy
+// of tile j+1 is in flight while tile j is computed.  A wave skips the MFMA work
+// of a chunk none of its tokens kept; rows of a wave that did not keep a chunk
+// get bias -inf for it, which keeps the per-token result exact.
+//
+// LDS layout.  Tiles are row major ([key][d], no padding: the direct copy writes
+// 1 KB contiguous per wave instruction) with the 16-byte chunks of every row
+// permuted by an XOR pattern chosen per tensor so that the operand reads below
+// are free of bank conflicts; the permutation is applied on the global side
+// (which chunk a lane fetches), so it costs nothing.
 //
 // MFMA formulation (v_mfma_f32_32x32x16_bf16, wave64).  Both products are
 // computed transposed so that no register shuffle is needed between them:
 //   S^T[key,row]  = K[key,:] . Q[row,:]      A = K tile (LDS), B = Q (registers)
-//   O^T[d,row]   += V^T[d,key] . P^T[key,row] A = V^T tile (LDS), B = P (registers)
+//   O^T[d,row]   += V^T[d,key] . P^T[key,row] A = V^T (LDS, transposing read), B = P
 // In the 32x32 accumulator layout lane (n = lane%32, h = lane/32) holds, for
 // row n, the 16 keys {8q + 4h + i}: exactly the operand-B slots of lane (n, h)
-// once the contraction index of the second product is permuted accordingly.
-// That permutation is applied for free when V is transposed into LDS (an 8x8
-// bf16 register transpose per thread).  Row max / row sum are in-lane plus one
-// cross-half exchange, and the O rescale is a per-lane scalar.
+// once the contraction index of the second product is ordered accordingly.  The
+// V^T operand is read from the row-major V tile with ds_read_b64_tr_b16, which
+// hands each lane four consecutive keys of one d column.  Row max / row sum are
+// in-lane plus one cross-half exchange, and the O rescale is a per-lane scalar.
 #include <math.h>
 #include <stdlib.h>
 
@@ -29,96 +35,100 @@
 
 #include "common.h"
 #include "dash_internal.h"
-
-// Two workgroups (8 waves) per CU: with <= 256 VGPRs per wave a second wave per
-// SIMD overlaps its softmax VALU work with the other wave's MFMAs.
-#ifndef DASH_S2_MIN_WG
-#define DASH_S2_MIN_WG 2
-#endif
+#include "stage2_args.h"
 
 namespace dash {
 
-struct S2Args {
-  const uint16_t* q; const uint16_t* k; const uint16_t* v; uint16_t* o;
-  const uint32_t* mask; const float* bias;
-  int h_q, h_kv, g_q, n_q, n_kv, block, t_all, words, pos0, causal, n_tiles, hb;
-  int64_t qs_b, qs_h, qs_t, ks_b, ks_h, ks_t, vs_b, vs_h, vs_t, os_b, os_h, os_t;
-  float c1;   // scale * log2(e)
-  float* part;   // decode partials
-};
-
-constexpr float kLazy = 8.f;   // lazy-rescale slack, in base-2 logit units
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
 
 template <int D> struct S2Cfg {
-  static constexpr int KLD = D + 8;          // bf16 elements per K row in LDS
-  static constexpr int VLD = 64 + 8;         // bf16 elements per V^T row in LDS
-  static constexpr int K_ELEMS = 64 * KLD;
-  static constexpr int V_ELEMS = D * VLD;
-  static constexpr int K_LOADS = (64 * D * 2 / 16) / 128;   // 16-byte loads per K-staging thread
-  static constexpr size_t LDS_BYTES = (size_t)2 * (K_ELEMS + V_ELEMS) * 2 + 5 * 64 * 4;
+  static constexpr int NCH = D / 8;                       // 16-byte chunks per row
+  static constexpr int ROW_BYTES = D * 2;
+  static constexpr int TILE_BYTES = 64 * ROW_BYTES;       // one K or V tile
+  static constexpr int COPIES = TILE_BYTES / 16 / 256;    // copy instructions per thread, tile and tensor
+  static constexpr int ROWS_PER_COPY = 256 / NCH;         // rows one copy instruction of the workgroup covers
+  static constexpr int MASK_OFF = 4 * TILE_BYTES;            // after the K ring [2] and the V ring [2]
+  static constexpr size_t LDS_BYTES = (size_t)MASK_OFF + 5 * 64 * 4;
 };
 
-// slot (position along the contraction index as stored in LDS) -> key offset
-// inside a 64-key tile: slot bits [g:2 | h:1 | i_hi:1 | i_lo:2] <-> key bits
-// [g:2 | i_hi:1 | h:1 | i_lo:2]
-__device__ __forceinline__ int slot_group_key(int sg, int i) {
-  return (sg >> 1) * 16 + (i >> 2) * 8 + (sg & 1) * 4 + (i & 3);
+// Chunk permutations (position of logical 16-byte chunk c of tile row `row`).
+// K: the A-operand read has lanes n = 0..15 on 16 consecutive rows at the same
+// logical chunk, so those rows must spread over all 16 chunk slots of a 256-byte
+// bank window.  V: the transposing read has 16 lanes on 4 consecutive rows x 4
+// consecutive chunks, so rows r..r+3 must land in different 64-byte groups.
+template <int D> __device__ __forceinline__ int k_swz(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D> __device__ __forceinline__ int v_swz(int row) {
+  return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
 }
 
-// RT: 32-row tiles per wave (1 or 2).  A wave owns 32*RT (token, head) rows; the
-// K / V^T fragments it reads from LDS are reused for its RT row tiles, so RT = 2
-// halves the LDS traffic per MFMA flop.
-//
-// DECODE: one query token per sequence (n_q == 1).  All four waves hold the same
-// g_q rows and compute the same S^T; wave w accumulates only the d-tile w of
-// O^T.  The workgroup handles the `split`-th share of the token's attended
-// chunks and writes an unnormalised partial (O, running max, running sum) that
-// a merge kernel combines (split-KV decoding, Sec. 3.5).
-template <int D, int RT, bool DENSE, bool DECODE>
-__global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a) {
-  using C = S2Cfg<D>;
-  static_assert(!DECODE || RT == 1, "decode uses one row tile");
-  extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-  uint16_t* Ks = lds;                               // [2][64][KLD]
-  uint16_t* Vt = lds + 2 * C::K_ELEMS;              // [2][D][VLD]
-  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + 2 * (C::K_ELEMS + C::V_ELEMS));  // [64]
-  uint32_t* wvmask = wgmask + 64;                   // [4][64]
+// Buffer resource (raw, no stride) over `bytes` bytes at p: loads past the end
+// return zero instead of touching memory.
+__device__ __forceinline__ u32x4 make_rsrc(const void* p, int64_t bytes) {
+  const uint64_t base = (uint64_t)p;
+  u32x4 rs;
+  rs[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
+  rs[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
+  rs[2] = __builtin_amdgcn_readfirstlane((uint32_t)bytes);
+  rs[3] = 0x00020000u;
+  return rs;
+}
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+// One wave copies 64 x 16 bytes from global memory straight into LDS: lane l
+// fetches 16 bytes at resource base + voff (per lane) + soff (uniform) and they
+// land at LDS byte address lds_addr (uniform) + 16 l.  The copy is counted by
+// vmcnt; it is issued from assembly so that the compiler does not order later
+// LDS reads of the other slots behind it, and the caller waits with
+// s_waitcnt vmcnt(0) before the barrier that publishes the slot.
+__device__ __forceinline__ void copy16_to_lds(u32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+
+template <int D, bool DENSE>
+__global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
+  using C = S2Cfg<D>;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + C::MASK_OFF);   // [64]
+  uint32_t* wvmask = wgmask + 64;                                      // [4][64]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 31, h = lane >> 5;
   // workgroup id -> (tile, kv-head, batch): consecutive ids walk the (head, batch)
   // pairs so that the 8 XCDs (round-robin dispatch) each see few distinct KV streams
   const int hbi = blockIdx.x % a.hb;
-  const int tile = a.n_tiles - 1 - blockIdx.x / a.hb;   // longest rows first; DECODE: split id
+  const int tile = a.n_tiles - 1 - blockIdx.x / a.hb;   // longest rows first
   const int r = hbi % a.h_kv, b = hbi / a.h_kv;
-  constexpr int WROWS = 32 * RT;                    // rows per wave
-  const int tokw = DECODE ? 1 : WROWS / a.g_q;      // tokens per wave
-  const int tok_w0 = DECODE ? 0 : tile * 4 * tokw + wave * tokw;   // first token of this wave
+  const int tokw = 32 / a.g_q;                          // tokens per wave
+  const int tok_w0 = tile * 4 * tokw + wave * tokw;     // first token of this wave
   const int nsub = a.block >> 6;
 
-  // ---- per-row constants (row tile rt, row n of it) -----------------------
-  int my_tok[RT], my_head[RT], row_pos[RT];
-  bool row_ok[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; rt++) {
-    const int row = rt * 32 + n;
-    my_tok[rt] = DECODE ? 0 : tok_w0 + row / a.g_q;
-    my_head[rt] = r * a.g_q + row % a.g_q;
-    row_ok[rt] = DECODE ? row < a.g_q : my_tok[rt] < a.n_q;
-    row_pos[rt] = a.pos0 + (row_ok[rt] ? my_tok[rt] : a.n_q - 1);
-  }
+  // ---- per-row constants ---------------------------------------------------
+  const int my_tok = tok_w0 + n / a.g_q;
+  const int my_head = r * a.g_q + n % a.g_q;
+  const bool row_ok = my_tok < a.n_q;
+  const int row_pos = a.pos0 + (row_ok ? my_tok : a.n_q - 1);
   // chunk of the wave's tokens (all tokens of a wave share it)
   const int cw = (a.pos0 + (tok_w0 < a.n_q ? tok_w0 : a.n_q - 1)) / a.block;
   const bool wave_ok = tok_w0 < a.n_q;
 
-  // ---- Q fragments (operand B of S^T = K Q^T) ----------------------------
-  bf16x8 qf[RT][D / 16];
+  // ---- Q fragments (operand B of S^T = K Q^T) ------------------------------
+  bf16x8 qf[D / 16];
+  {
+    const uint16_t* qp = a.q + b * a.qs_b + my_head * a.qs_h +
+                         (int64_t)(row_ok ? my_tok : a.n_q - 1) * a.qs_t + h * 8;
 #pragma unroll
-  for (int rt = 0; rt < RT; rt++) {
-    const uint16_t* qp = a.q + b * a.qs_b + my_head[rt] * a.qs_h +
-                         (int64_t)(row_ok[rt] ? my_tok[rt] : a.n_q - 1) * a.qs_t + h * 8;
+    for (int ks = 0; ks < D / 16; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    // the loads must be complete (and known to be) before the tile loop: a wait for
+    // them inside the loop would also wait for the tile copies in flight
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) qf[rt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    for (int ks = 0; ks < D / 16; ks++) asm volatile("" : "+v"(qf[ks]));
   }
 
   // ---- chunk bitmaps -------------------------------------------------------
@@ -158,39 +168,7 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
       }
   }
   __syncthreads();
-  if (DECODE) {
-    // keep only this split's share of the attended chunks: entries
-    // [e0, e1) of the ascending list.  Wave 0: lane wi owns mask word wi.
-    if (wave == 0) {
-      const uint32_t w0 = wgmask[lane];
-      const int pc = __popc(w0);
-      int incl = pc;                               // inclusive prefix sum over lanes
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-      }
-      const int total = __shfl(incl, 63);
-      const int per = (total + a.n_tiles - 1) / a.n_tiles;
-      const int e0 = tile * per, e1 = min(total, e0 + per);
-      const int start = incl - pc;                 // rank of this word's first set bit
-      uint32_t w = w0;
-      int drop = e0 - start;                       // set bits to clear from the bottom
-      for (int i = 0; i < drop && w; i++) w &= w - 1u;
-      int keep = e1 - max(start, e0);              // set bits to keep after that
-      uint32_t kept = 0u;
-      for (int i = 0; i < keep && w; i++) { kept |= w & (0u - w); w &= w - 1u; }
-      wgmask[lane] = kept;
-      if (lane == 0) wvmask[0] = (uint32_t)min(e0, total);   // rank of the split's first entry
-    }
-    __syncthreads();
-    trk_rank = (int)wvmask[0];
-    __syncthreads();
-    // every wave participates in every kept chunk
-    for (int i = tid; i < 64; i += 256) { const uint32_t w = wgmask[i]; wvmask[i] = w; wvmask[64 + i] = w; wvmask[128 + i] = w; wvmask[192 + i] = w; }
-    __syncthreads();
-  }
-  if (!DENSE && !DECODE && trk_ok && trk_rank < a.t_all) trk_next = trk_bias[trk_rank];
+  if (!DENSE && trk_ok && trk_rank < a.t_all) trk_next = trk_bias[trk_rank];
 
   // ---- tile iterator (workgroup-uniform) ---------------------------------
   int it_wi = -1, it_sub = nsub - 1, it_u = -1;
@@ -207,118 +185,69 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
     return true;
   };
 
-  // ---- staging -------------------------------------------------------------
-  // Threads 0..127 stage K (row-major copy), threads 128..255 stage V (8x8 bf16
-  // register transpose into the permuted V^T layout).  Every load address is
-  // "uniform tile base + uniform per-load stride + per-thread byte offset", so the
-  // per-tile address arithmetic is scalar.
-  const bool stage_k = tid < 128;
-  const int st = tid & 127;
-  const char* kbase = reinterpret_cast<const char*>(a.k + b * a.ks_b + r * a.ks_h);
-  const char* vbase = reinterpret_cast<const char*>(a.v + b * a.vs_b + r * a.vs_h);
-  u32x4 sreg[8];
-  u32x4 sreg2[DECODE ? 8 : 1];   // decode: second set, tiles are fetched two ahead
-  const int v_sg = st & 7, v_dg = st >> 3;          // V: slot group, 8-column group
-  constexpr int KROWS = 128 / (D / 8);              // K rows covered by one load of the 128 threads
-  const int k_row0 = st / (D / 8), k_col = (st % (D / 8)) * 8;
-  const int v_row0 = (v_sg >> 1) * 16 + (v_sg & 1) * 4;
-  const uint32_t k_toff = (uint32_t)(k_row0 * a.ks_t + k_col) * 2u;     // bytes
-  const uint32_t v_toff = (uint32_t)(v_row0 * a.vs_t + v_dg * 8) * 2u;
-  const bool v_active = v_dg < D / 8;
-  auto stage_load = [&](int u, int sub, u32x4 (&sreg)[8]) {
-    const int kpos0 = u * a.block + sub * 64;
-    if (kpos0 + 64 <= a.n_kv) {
-      if (stage_k) {
-        const char* tb = kbase + (int64_t)kpos0 * a.ks_t * 2;
+  // ---- global -> LDS tile copies -------------------------------------------
+  // Copy instruction i of wave w fills the 1 KB LDS segment (4i + w): slot
+  // s = (4i + w) * 64 + lane, tile row s / NCH, chunk position s % NCH, which
+  // receives logical chunk pos ^ swz(row) of that row.  The swizzle depends only
+  // on (w, lane), so each thread keeps one byte offset per tensor; the tile and
+  // instruction offsets are scalar (buffer addressing: resource + lane offset +
+  // scalar offset).  The resource ends with the last key, so the rows a ragged
+  // last tile has beyond n_kv read as zeros instead of touching memory.
+  const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
+  const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
+  const uint32_t k_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ k_swz<D>(c_row)) << 4));
+  const uint32_t v_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ v_swz<D>(c_row)) << 4));
+  const uint32_t k_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.ks_t * 2);
+  const uint32_t v_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.vs_t * 2);
+  auto copy_k = [&](int u, int sub, int slot) {
+    const uint32_t dst = lds0 + slot * C::TILE_BYTES + wave * 1024;
+    const uint32_t tk = (uint32_t)(u * a.block + sub * 64) * (uint32_t)a.ks_t * 2u;
 #pragma unroll
-        for (int i = 0; i < C::K_LOADS; i++)
-          sreg[i] = *reinterpret_cast<const u32x4*>(tb + (int64_t)i * KROWS * a.ks_t * 2 + k_toff);
-      } else if (v_active) {
-        const char* tb = vbase + (int64_t)kpos0 * a.vs_t * 2;
-#pragma unroll
-        for (int i = 0; i < 8; i++)
-          sreg[i] = *reinterpret_cast<const u32x4*>(tb + (int64_t)((i >> 2) * 8 + (i & 3)) * a.vs_t * 2 + v_toff);
-      }
-    } else {
-      // ragged last tile: clamp the row index (those keys are masked later)
-      if (stage_k) {
-#pragma unroll
-        for (int i = 0; i < C::K_LOADS; i++) {
-          int key = kpos0 + i * KROWS + k_row0;
-          key = key < a.n_kv ? key : a.n_kv - 1;
-          sreg[i] = *reinterpret_cast<const u32x4*>(kbase + ((int64_t)key * a.ks_t + k_col) * 2);
-        }
-      } else if (v_active) {
-#pragma unroll
-        for (int i = 0; i < 8; i++) {
-          int key = kpos0 + slot_group_key(v_sg, i);
-          key = key < a.n_kv ? key : a.n_kv - 1;
-          sreg[i] = *reinterpret_cast<const u32x4*>(vbase + ((int64_t)key * a.vs_t + v_dg * 8) * 2);
-        }
-      }
-    }
+    for (int i = 0; i < C::COPIES; i++) copy16_to_lds(k_rs, dst + i * 4096, k_off, tk + i * k_step);
   };
-  uint16_t* const k_dst0 = Ks + k_row0 * C::KLD + k_col;
-  uint16_t* const v_dst0 = Vt + (v_dg * 8) * C::VLD + v_sg * 8;
-  auto stage_store = [&](int buf, const u32x4 (&sreg)[8]) {
-    if (stage_k) {
-      uint16_t* dst = k_dst0 + buf * C::K_ELEMS;
+  auto copy_v = [&](int u, int sub, int slot) {
+    const uint32_t dst = lds0 + (2 + slot) * C::TILE_BYTES + wave * 1024;
+    const uint32_t tv = (uint32_t)(u * a.block + sub * 64) * (uint32_t)a.vs_t * 2u;
 #pragma unroll
-      for (int i = 0; i < C::K_LOADS; i++)
-        *reinterpret_cast<u32x4*>(dst + i * KROWS * C::KLD) = sreg[i];
-    } else if (v_active) {
-      uint16_t* dst = v_dst0 + buf * C::V_ELEMS;
-      // 8x8 bf16 transpose: column e of the 8 loaded rows becomes one 16-byte row
-#pragma unroll
-      for (int e = 0; e < 8; e++) {
-        u32x4 o;
-#pragma unroll
-        for (int i2 = 0; i2 < 4; i2++) {
-          const uint32_t lo = sreg[2 * i2][e >> 1], hi = sreg[2 * i2 + 1][e >> 1];
-          // byte select: low halves {hi[1:0], lo[1:0]} or high halves {hi[3:2], lo[3:2]}
-          o[i2] = __builtin_amdgcn_perm(hi, lo, (e & 1) ? 0x07060302u : 0x05040100u);
-        }
-        *reinterpret_cast<u32x4*>(dst + e * C::VLD) = o;
-      }
-    }
+    for (int i = 0; i < C::COPIES; i++) copy16_to_lds(v_rs, dst + i * 4096, v_off, tv + i * v_step);
   };
+
+  // ---- operand read addresses (bytes inside a stage) -------------------------
+  // K, A operand of S^T: lane (n, h) reads logical chunk 2 ks + h of rows n, 32 + n
+  uint32_t k_rd[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++)
+    k_rd[ks] = (uint32_t)(n * C::ROW_BYTES + (((2 * ks + h) ^ k_swz<D>(n)) << 4));
+  // V, A operand of O^T (transposing read): lanes 16 g .. 16 g + 15 serve d
+  // columns 16 (g & 1) .. + 15 of a d-tile and contraction half h = g >> 1; lane
+  // s of the group points at key row 4 h + s / 4, d offset 16 (g & 1) + 4 (s % 4)
+  // of d-tile t, which the row's swizzle moved to 64-byte group t ^ swz(row).
+  const int s16 = lane & 15, a16 = (lane >> 4) & 1;
+  uint32_t v_rd[D / 32];
+#pragma unroll
+  for (int t = 0; t < D / 32; t++)
+    v_rd[t] = (uint32_t)((4 * h + (s16 >> 2)) * C::ROW_BYTES +
+                         ((((4 * t) ^ v_swz<D>(s16 >> 2)) + 2 * a16 + ((s16 & 3) >> 1)) << 4) + ((s16 & 1) << 3));
 
   // ---- online-softmax state (base-2 logits) -------------------------------
-  float m_run[RT], l_run[RT];
-  constexpr int NDT = DECODE ? 1 : D / 32;
-  f32x16 oacc[RT][NDT];
+  float m_run = -INFINITY, l_run = 0.f;
+  constexpr int NDT = D / 32;
+  f32x16 oacc[NDT];
 #pragma unroll
-  for (int rt = 0; rt < RT; rt++) {
-    m_run[rt] = -INFINITY; l_run[rt] = 0.f;
+  for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
-    for (int dt = 0; dt < NDT; dt++)
-#pragma unroll
-      for (int j = 0; j < 16; j++) oacc[rt][dt][j] = 0.f;
-  }
+    for (int j = 0; j < 16; j++) oacc[dt][j] = 0.f;
 
-  float bias_row[RT];   // bias * log2e of this lane's rows for the current chunk
-#pragma unroll
-  for (int rt = 0; rt < RT; rt++) bias_row[rt] = 0.f;
+  float bias_row = 0.f;   // bias * log2e of this lane's row for the current chunk
   bool wave_on = false, diag = false;
-
-  // DECODE: one token per workgroup, so the bias list is walked with wave-uniform
-  // (scalar) loads; they do not queue behind the vector loads of the tile prefetch.
-  const float* dec_bias = DENSE ? nullptr : a.bias + (((int64_t)b * a.h_kv + r) * a.n_q) * a.t_all;
-  int dec_rank = DECODE ? __builtin_amdgcn_readfirstlane(trk_rank) : 0;
 
   auto begin_chunk = [&](int u) {
     // decides participation and fetches the per-token bias of chunk u
     wave_on = wave_ok && ((__builtin_amdgcn_readfirstlane(wvmask[wave * 64 + (u >> 5)]) >> (u & 31)) & 1u);
     diag = a.causal && u == cw;
     if (!wave_on) return;
-    if constexpr (DECODE) {
-      // every chunk this workgroup visits is one of the token's attended chunks,
-      // in list order; padded rows simply share the bias
-      float bt = 0.f;
-      if (!DENSE && !diag) { bt = dec_bias[dec_rank] * kLog2e; dec_rank++; }
-      bias_row[0] = bt;
-      return;
-    }
     float bt = 0.f;
     if (!DENSE && !diag) {
       bt = -INFINITY;
@@ -331,207 +260,187 @@ __global__ __launch_bounds__(256, DASH_S2_MIN_WG) void s2_attend_kernel(S2Args a
         }
       }
     }
-#pragma unroll
-    for (int rt = 0; rt < RT; rt++) bias_row[rt] = __shfl(bt, (rt * 32 + n) / a.g_q);
+    bias_row = __shfl(bt, n / a.g_q);
   };
 
-  // One 64-key tile: S^T = K Q^T, online softmax, O^T += V^T P^T.  MASKED adds
-  // the causal / sequence-end key mask (diagonal chunk and ragged tail only).
-  auto compute = [&](int buf, int kpos0, auto masked_tag) {
-    constexpr bool MASKED = decltype(masked_tag)::value;
-    const uint16_t* Kb = Ks + buf * C::K_ELEMS + n * C::KLD + h * 8;
-    const uint16_t* Vb = Vt + buf * C::V_ELEMS + n * C::VLD + h * 8;
-    f32x16 s[RT][2];
+  // ---- one 64-key tile -------------------------------------------------------
+  // S^T = K Q^T, online softmax, O^T += V^T P^T.  The source is written slot by
+  // slot (one MFMA per slot, its operand reads a few slots ahead, a share of the
+  // softmax VALU work behind it) in the order the instructions should issue, and
+  // the scheduler may not move code across slots.  VALU budget: an MFMA 32x32x16
+  // leaves about 24 issue cycles of its 32, an exponential takes 8 and a plain
+  // VALU op 4.  P = LDS slot of the tile (compile time: every LDS offset is an
+  // immediate).  MASKED adds the causal / sequence-end key mask (diagonal chunk
+  // and ragged tail only).
+  auto tile_math = [&](auto p_tag, auto m_tag, int kpos0) {
+    constexpr int P = decltype(p_tag)::value;
+    constexpr bool MASKED = decltype(m_tag)::value;
+    constexpr int NS = D / 8;                                 // MFMAs per product and tile
+    const char* kb = lds + P * C::TILE_BYTES;                  // K ring
+    const char* vb = lds + (2 + P) * C::TILE_BYTES;            // V ring
+    auto k_read = [&](int i) -> bf16x8 {   // slot i: d slice i / 2, key half i % 2
+      return *reinterpret_cast<const bf16x8*>(kb + k_rd[i >> 1] + (i & 1) * 32 * C::ROW_BYTES);
+    };
+    auto v_read = [&](int i) -> bf16x8 {   // slot i: contraction step g = i / NDT, d-tile t = i % NDT
+      const int g = i / NDT, t = i % NDT;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(vb + v_rd[t] + (16 * g) * C::ROW_BYTES));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4*)(vb + v_rd[t] + (16 * g + 8) * C::ROW_BYTES));
+      return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    constexpr int KAHEAD = 4, VAHEAD = 2;
+    f32x16 s[2];
+    {
+      bf16x8 kf[NS];
 #pragma unroll
-    for (int rt = 0; rt < RT; rt++)
+      for (int i = 0; i < KAHEAD; i++) kf[i] = k_read(i);
 #pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int j = 0; j < 16; j++) s[rt][kt][j] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ks++)
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(Kb + kt * 32 * C::KLD + ks * 16);
-#pragma unroll
-        for (int rt = 0; rt < RT; rt++)
-          s[rt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[rt][ks], s[rt][kt], 0, 0, 0);
-      }
-    bf16x8 pb[RT][4];
-    bool grow = false;
-    float tmax[RT];
-#pragma unroll
-    for (int rt = 0; rt < RT; rt++) {
-      float mloc = -INFINITY;
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int j = 0; j < 16; j++) {
-          if constexpr (MASKED) {
-            const int kp = kpos0 + kt * 32 + (j >> 2) * 8 + h * 4 + (j & 3);
-            const bool dead = (diag && kp > row_pos[rt]) || kp >= a.n_kv;
-            s[rt][kt][j] = dead ? -INFINITY : s[rt][kt][j];
-          }
-          mloc = fmaxf(mloc, s[rt][kt][j]);
+      for (int i = 0; i < NS; i++) {
+        if (i + KAHEAD < NS) kf[i + KAHEAD] = k_read(i + KAHEAD);
+        const int ks = i >> 1, kt = i & 1;
+        if (ks == 0) {
+          const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[ks], z, 0, 0, 0);
+        } else {
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], qf[ks], s[kt], 0, 0, 0);
         }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-      // max of the base-2 logits s*c1 + bias over the tile (c1 > 0)
-      tmax[rt] = fmaf(mloc, a.c1, bias_row[rt]);
-      grow = grow || (tmax[rt] > m_run[rt] + kLazy);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
+    float mloc = -INFINITY;
+    // MASKED: key kpos0 + 4 h + c (c = the compile-time part of the key index of
+    // an accumulator register) is dead if it lies after the row's position in the
+    // diagonal chunk or past the end of the sequence, i.e. if c > lim
+    int lim = 0;
+    if constexpr (MASKED) {
+      const int k0 = kpos0 + 4 * h;
+      lim = min(diag ? row_pos - k0 : 0x7fffffff, a.n_kv - 1 - k0);
+      asm volatile("" : "+v"(lim));   // keep the per-register comparisons against immediates
+    }
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+      for (int j = 0; j < 16; j += 2) {
+        if constexpr (MASKED) {
+#pragma unroll
+          for (int jj = j; jj < j + 2; jj++) {
+            const int c = kt * 32 + (jj >> 2) * 8 + (jj & 3);
+            s[kt][jj] = c > lim ? -INFINITY : s[kt][jj];
+          }
+        }
+        mloc = fmaxf(fmaxf(mloc, s[kt][j]), s[kt][j + 1]);
+      }
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+    // max of the base-2 logits s*c1 + bias over the tile (c1 > 0)
+    const float tmax = fmaf(mloc, a.c1, bias_row);
     // Lazy rescaling: the reference max m_run of a row is only raised when the
     // tile's max exceeds it by more than 2^kLazy; until then p = 2^(t - m_run)
     // may reach 2^kLazy, which fp32 / bf16 hold without loss, and the final
     // division by the row sum is unaffected.  Raising it is rare after the
     // first tiles, so the O rescale below is almost never executed.
-    if (__any(grow)) {
-#pragma unroll
-      for (int rt = 0; rt < RT; rt++) {
-        const float m_new = fmaxf(m_run[rt], tmax[rt]);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float corr = __builtin_amdgcn_exp2f(m_run[rt] - m_use);   // m_run = -inf -> 0
-        m_run[rt] = m_new;
-        l_run[rt] *= corr;
-#pragma unroll
-        for (int dt = 0; dt < NDT; dt++)
-#pragma unroll
-          for (int j = 0; j < 16; j++) oacc[rt][dt][j] *= corr;
-      }
-    }
-#pragma unroll
-    for (int rt = 0; rt < RT; rt++) {
-      const float off = bias_row[rt] - (m_run[rt] == -INFINITY ? 0.f : m_run[rt]);
-      float lsum = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-        for (int j = 0; j < 16; j++) {
-          const float pj = __builtin_amdgcn_exp2f(fmaf(s[rt][kt][j], a.c1, off));
-          lsum += pj;
-          pb[rt][kt * 2 + (j >> 3)][j & 7] = (__bf16)pj;
-        }
-      l_run[rt] += lsum;
-    }
-    if constexpr (DECODE) {
-      if (wave < D / 32) {
-#pragma unroll
-        for (int g = 0; g < 4; g++) {
-          const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vb + wave * 32 * C::VLD + g * 16);
-          oacc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[0][g], oacc[0][0], 0, 0, 0);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int g = 0; g < 4; g++)
-#pragma unroll
-        for (int dt = 0; dt < D / 32; dt++) {
-          const bf16x8 va = *reinterpret_cast<const bf16x8*>(Vb + dt * 32 * C::VLD + g * 16);
-#pragma unroll
-          for (int rt = 0; rt < RT; rt++)
-            oacc[rt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[rt][g], oacc[rt][dt], 0, 0, 0);
-        }
-    }
-  };
-
-  // ---- main loop -----------------------------------------------------------
-  auto run_tile = [&](int cu, int csub, int buf) {
-    if (wave_on) {
-      const int kpos0 = cu * a.block + csub * 64;
-      if (diag || kpos0 + 64 > a.n_kv) compute(buf, kpos0, std::true_type{});
-      else compute(buf, kpos0, std::false_type{});
-    }
-  };
-  int buf = 0;
-  if constexpr (!DECODE) {
-    bool have = advance();
-    if (have) {
-      stage_load(it_u, it_sub, sreg);
-      stage_store(0, sreg);
-    }
-    __syncthreads();
-    while (have) {
-      const int cu = it_u, csub = it_sub;
-      const bool more = advance();
-      // bias bookkeeping first: its wait on the previously prefetched bias must not
-      // also wait for the tile loads issued next
-      if (csub == 0) begin_chunk(cu);
-      if (more) stage_load(it_u, it_sub, sreg);
-      run_tile(cu, csub, buf);
-      if (more) stage_store(buf ^ 1, sreg);
-      __syncthreads();
-      buf ^= 1;
-      have = more;
-    }
-  } else {
-    // Decode is bound by HBM latency x bandwidth, not by compute: keep two tiles
-    // (64 KB per workgroup) in flight.  While tile j is computed from LDS, tile
-    // j+1 and tile j+2 are on their way into the two register sets, which swap
-    // roles every iteration (the loop body is written out twice).
-    bool have0 = advance();
-    int u0 = it_u, s0 = it_sub;
-    if (have0) { stage_load(u0, s0, sreg); stage_store(0, sreg); }
-    bool have1 = have0 && advance();
-    int u1 = it_u, s1 = it_sub;
-    if (have1) stage_load(u1, s1, sreg);
-    bool have2 = have1 && advance();
-    int u2 = it_u, s2 = it_sub;
-    if (have2) stage_load(u2, s2, sreg2);
-    __syncthreads();
-    auto step = [&](u32x4 (&pr)[8]) {
-      // pr holds tile j+1 (if any); after it is stored it receives tile j+3
-      if (s0 == 0) begin_chunk(u0);
-      run_tile(u0, s0, buf);
-      if (have1) stage_store(buf ^ 1, pr);
-      const bool have3 = have2 && advance();
-      if (have3) stage_load(it_u, it_sub, pr);
-      __syncthreads();
-      buf ^= 1;
-      have0 = have1; u0 = u1; s0 = s1;
-      have1 = have2; u1 = u2; s1 = s2;
-      have2 = have3; u2 = it_u; s2 = it_sub;
-    };
-    while (have0) {
-      step(sreg);
-      if (!have0) break;
-      step(sreg2);
-    }
-  }
-
-  // ---- finalise ------------------------------------------------------------
-#pragma unroll
-  for (int rt = 0; rt < RT; rt++) {
-    const float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 32);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if constexpr (DECODE) {
-      // partial record per (batch, kv-head, split, head-in-group): D floats of
-      // unnormalised O, then the running max (base-2 logits) and the running sum
-      if (row_ok[0] && wave < D / 32) {
-        float* pp = a.part + ((((int64_t)b * a.h_kv + r) * a.n_tiles + tile) * a.g_q + n) * (D + 2);
-#pragma unroll
-        for (int j = 0; j < 16; j++)
-          pp[wave * 32 + (j >> 2) * 8 + h * 4 + (j & 3)] = oacc[0][0][j];
-        if (wave == 0 && h == 0) { pp[D] = m_run[0]; pp[D + 1] = l_tot; }
-      }
-    } else if (row_ok[rt]) {
-      uint16_t* op = a.o + b * a.os_b + my_head[rt] * a.os_h + (int64_t)my_tok[rt] * a.os_t;
+    if (__any(tmax > m_run + kLazy)) {
+      const float m_new = fmaxf(m_run, tmax);
+      const float m_use = m_new == -INFINITY ? 0.f : m_new;
+      const float corr = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
+      m_run = m_new;
+      l_run *= corr;
 #pragma unroll
       for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          const int d0 = dt * 32 + q4 * 8 + h * 4;
-          uint2 w;
-          w.x = pack_bf16x2(oacc[rt][dt][q4 * 4 + 0] * inv, oacc[rt][dt][q4 * 4 + 1] * inv);
-          w.y = pack_bf16x2(oacc[rt][dt][q4 * 4 + 2] * inv, oacc[rt][dt][q4 * 4 + 3] * inv);
-          *reinterpret_cast<uint2*>(op + d0) = w;
-        }
+        for (int j = 0; j < 16; j++)   // in place: the accumulators must not move between registers
+          asm volatile("v_mul_f32 %0, %1, %0" : "+v"(oacc[dt][j]) : "v"(corr));
     }
+    const float off = bias_row - (m_run == -INFINITY ? 0.f : m_run);
+    u32x4 pb[4];
+    float lsum = 0.f;
+    // exponential pair k: P^T slots 2 (k % 4), + 1 of contraction step g = k / 4
+    auto e_pair = [&](int k) {
+      const int g = k >> 2, kt = g >> 1, j = 8 * (g & 1) + 2 * (k & 3);
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, off));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][j + 1], a.c1, off));
+      lsum += p0 + p1;
+      asm volatile("" : "+v"(lsum));   // keeps the row-sum update in its slot
+      const bf16x2 w = {(__bf16)p0, (__bf16)p1};
+      pb[g][k & 3] = __builtin_bit_cast(uint32_t, w);
+    };
+    {
+      bf16x8 vf[NS];
+#pragma unroll
+      for (int i = 0; i < VAHEAD; i++) vf[i] = v_read(i);
+#pragma unroll
+      for (int k = 0; k < 4; k++) e_pair(k);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < NS; i++) {
+        if (i + VAHEAD < NS) vf[i + VAHEAD] = v_read(i + VAHEAD);
+        const int g = i / NDT, t = i % NDT;
+        oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], __builtin_bit_cast(bf16x8, pb[g]), oacc[t], 0, 0, 0);
+        // the remaining 12 pairs go behind the first MFMAs: pairs of step g + 1
+        // must be complete before slot NDT * (g + 1)
+        constexpr int PPS = D == 128 ? 1 : 2;
+#pragma unroll
+        for (int kk = 0; kk < PPS; kk++)
+          if (4 + i * PPS + kk < 16) e_pair(4 + i * PPS + kk);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    l_run += lsum;
+  };
+
+  // ---- main loop -----------------------------------------------------------
+  // LDS: K ring [2] then V ring [2]; tile j lives in slot j & 1 of both.  At the
+  // top of iteration j the wave waits for its own copies of tile j, the barrier
+  // makes everybody's copies visible and guarantees that tile j - 1 (the other
+  // slot) is no longer read; then the copies of tile j + 1 start and run during
+  // the computation of tile j.  The loop body is written out twice so that the
+  // slot is a compile-time constant.
+  bool have = advance();
+  if (have) { copy_k(it_u, it_sub, 0); copy_v(it_u, it_sub, 0); }
+  auto iteration = [&](auto p_tag) {
+    constexpr int P = decltype(p_tag)::value;
+    const int cu = it_u, csub = it_sub;
+    const bool more = advance();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's copies of tile j have landed
+    __syncthreads();
+    if (csub == 0) begin_chunk(cu);
+    if (more) { copy_k(it_u, it_sub, P ^ 1); copy_v(it_u, it_sub, P ^ 1); }
+    if (wave_on) {
+      const int kpos0 = cu * a.block + csub * 64;
+      if (diag || kpos0 + 64 > a.n_kv) tile_math(p_tag, std::true_type{}, kpos0);
+      else tile_math(p_tag, std::false_type{}, kpos0);
+    }
+    have = more;
+  };
+  while (have) {
+    iteration(std::integral_constant<int, 0>{});
+    if (!have) break;
+    iteration(std::integral_constant<int, 1>{});
+  }
+
+  // ---- finalise ------------------------------------------------------------
+  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  if (row_ok) {
+    uint16_t* op = a.o + b * a.os_b + my_head * a.os_h + (int64_t)my_tok * a.os_t;
+#pragma unroll
+    for (int t = 0; t < NDT; t++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        // accumulator t, registers 4 q4 .. + 3: O^T rows 8 q4 + 4 h + i of d-tile t
+        const int m0 = q4 * 8 + h * 4;
+        uint2 w;
+        w.x = pack_bf16x2(oacc[t][q4 * 4 + 0] * inv, oacc[t][q4 * 4 + 1] * inv);
+        w.y = pack_bf16x2(oacc[t][q4 * 4 + 2] * inv, oacc[t][q4 * 4 + 3] * inv);
+        *reinterpret_cast<uint2*>(op + t * 32 + m0) = w;
+      }
   }
 }
 
-template <int D, int RT, bool DENSE, bool DECODE>
+template <int D, bool DENSE>
 static hipError_t launch_s2_t(const S2Args& a, hipStream_t st) {
   using C = S2Cfg<D>;
-  auto kern = s2_attend_kernel<D, RT, DENSE, DECODE>;
+  auto kern = s2_attend_kernel<D, DENSE>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -543,97 +452,15 @@ static hipError_t launch_s2_t(const S2Args& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Row tiles per wave; DASH_S2_ROW_TILES / DASH_DENSE_ROW_TILES = 1|2 override (tuning aids).
-static int env_row_tiles(const char* name, int dflt) {
-  const char* e = getenv(name);
-  if (e && e[0] == '1') return 1;
-  if (e && e[0] == '2') return 2;
-  return dflt;
-}
-static int s2_sparse_row_tiles() {
-  static int v = env_row_tiles("DASH_S2_ROW_TILES", 1);
-  return v;
-}
-static int s2_dense_row_tiles() {
-  static int v = env_row_tiles("DASH_DENSE_ROW_TILES", 1);
-  return v;
-}
-
-static void fill_args(S2Args& a, const dash_params& p, const Layout& L, const void* q, const void* k,
-                      const void* v, void* o, const uint32_t* mask, const float* bias) {
-  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.o = (uint16_t*)o;
-  a.mask = mask; a.bias = bias; a.part = nullptr;
-  a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv;
-  a.block = p.block_size; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0;
-  a.causal = p.causal;
-  a.hb = p.h_kv * p.batch;
-  a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
-  a.ks_b = p.k_stride[0]; a.ks_h = p.k_stride[1]; a.ks_t = p.k_stride[2];
-  a.vs_b = p.v_stride[0]; a.vs_h = p.v_stride[1]; a.vs_t = p.v_stride[2];
-  a.os_b = p.o_stride[0]; a.os_h = p.o_stride[1]; a.os_t = p.o_stride[2];
-  a.c1 = L.scale * kLog2e;
-}
-
 hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, const void* k,
                           const void* v, void* o, const uint32_t* mask, const float* bias,
                           bool dense, hipStream_t st) {
   S2Args a;
-  fill_args(a, p, L, q, k, v, o, mask, bias);
-  // 32-row waves by default: they fit 256 VGPRs, so two workgroups share a CU.
-  // The 64-row variant halves the LDS bytes per flop but needs a whole SIMD's
-  // register file per wave; it is kept as a tuning option.
-  const int rt = dense ? s2_dense_row_tiles() : s2_sparse_row_tiles();
-  const int tok_tile = 4 * (32 * rt / L.g_q);
+  fill_s2_args(a, p, L, q, k, v, o, mask, bias);
+  const int tok_tile = 4 * (32 / L.g_q);
   a.n_tiles = (p.n_q + tok_tile - 1) / tok_tile;
-#define DASH_S2(D_)                                                                              \
-  (rt == 2 ? (dense ? launch_s2_t<D_, 2, true, false>(a, st) : launch_s2_t<D_, 2, false, false>(a, st)) \
-           : (dense ? launch_s2_t<D_, 1, true, false>(a, st) : launch_s2_t<D_, 1, false, false>(a, st)))
-  if (p.head_dim == 128) return DASH_S2(128);
-  return DASH_S2(64);
-#undef DASH_S2
-}
-
-// Merge of the split-KV partials: o = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
-template <typename T>
-__global__ __launch_bounds__(128) void decode_merge_kernel(const float* __restrict__ part,
-                                                           T* __restrict__ o, int h_q, int h_kv,
-                                                           int g_q, int splits, int d,
-                                                           int64_t os_b, int64_t os_h) {
-  const int head = blockIdx.x, b = blockIdx.y;
-  const int r = head / g_q, hl = head % g_q;
-  const int col = threadIdx.x;
-  const int rec = d + 2;
-  const float* base = part + (((int64_t)b * h_kv + r) * splits * g_q + hl) * rec;
-  float M = -INFINITY;
-  for (int s = 0; s < splits; s++) M = fmaxf(M, base[(int64_t)s * g_q * rec + d]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < splits; s++) {
-    const float* ps = base + (int64_t)s * g_q * rec;
-    const float m = ps[d];
-    const float w = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
-    den += w * ps[d + 1];
-    if (col < d && w > 0.f) num += w * ps[col];
-  }
-  if (col < d) elem<T>::st(o + b * os_b + head * os_h + col, num / den);
-}
-
-hipError_t launch_decode_s2(const dash_params& p, const Layout& L, const void* q, const void* k,
-                            const void* v, void* o, const uint32_t* mask, const float* bias,
-                            float* partials, bool dense, hipStream_t st) {
-  S2Args a;
-  fill_args(a, p, L, q, k, v, o, mask, bias);
-  a.n_tiles = L.splits;
-  a.part = partials;
-  hipError_t e;
-  if (p.head_dim == 128)
-    e = dense ? launch_s2_t<128, 1, true, true>(a, st) : launch_s2_t<128, 1, false, true>(a, st);
-  else
-    e = dense ? launch_s2_t<64, 1, true, true>(a, st) : launch_s2_t<64, 1, false, true>(a, st);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(decode_merge_kernel<uint16_t>, dim3(p.h_q, p.batch), dim3(128), 0, st, partials,
-                     (uint16_t*)o, p.h_q, p.h_kv, L.g_q, L.splits, p.head_dim, p.o_stride[0],
-                     p.o_stride[1]);
-  return hipGetLastError();
+  if (p.head_dim == 128) return dense ? launch_s2_t<128, true>(a, st) : launch_s2_t<128, false>(a, st);
+  return dense ? launch_s2_t<64, true>(a, st) : launch_s2_t<64, false>(a, st);
 }
 
 }  // namespace dash
