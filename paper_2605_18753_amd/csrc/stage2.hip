@@ -201,17 +201,18 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
   const uint32_t v_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ v_swz<D>(c_row)) << 4));
   const uint32_t k_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.ks_t * 2);
   const uint32_t v_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.vs_t * 2);
-  auto copy_k = [&](int u, int sub, int slot) {
-    const uint32_t dst = lds0 + slot * C::TILE_BYTES + wave * 1024;
-    const uint32_t tk = (uint32_t)(u * a.block + sub * 64) * (uint32_t)a.ks_t * 2u;
-#pragma unroll
-    for (int i = 0; i < C::COPIES; i++) copy16_to_lds(k_rs, dst + i * 4096, k_off, tk + i * k_step);
+  // copy instruction c of a tile: c < COPIES moves K rows, the rest V rows
+  uint32_t cp_k = 0, cp_v = 0;   // scalar byte offsets of the tile being copied
+  auto copy_begin = [&](int u, int sub) {
+    cp_k = (uint32_t)(u * a.block + sub * 64) * (uint32_t)a.ks_t * 2u;
+    cp_v = (uint32_t)(u * a.block + sub * 64) * (uint32_t)a.vs_t * 2u;
   };
-  auto copy_v = [&](int u, int sub, int slot) {
-    const uint32_t dst = lds0 + (2 + slot) * C::TILE_BYTES + wave * 1024;
-    const uint32_t tv = (uint32_t)(u * a.block + sub * 64) * (uint32_t)a.vs_t * 2u;
-#pragma unroll
-    for (int i = 0; i < C::COPIES; i++) copy16_to_lds(v_rs, dst + i * 4096, v_off, tv + i * v_step);
+  auto copy_one = [&](int c, int slot) {
+    if (c < C::COPIES)
+      copy16_to_lds(k_rs, lds0 + slot * C::TILE_BYTES + wave * 1024 + c * 4096, k_off, cp_k + c * k_step);
+    else
+      copy16_to_lds(v_rs, lds0 + (2 + slot) * C::TILE_BYTES + wave * 1024 + (c - C::COPIES) * 4096, v_off,
+                    cp_v + (c - C::COPIES) * v_step);
   };
 
   // ---- operand read addresses (bytes inside a stage) -------------------------
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
   // VALU op 4.  P = LDS slot of the tile (compile time: every LDS offset is an
   // immediate).  MASKED adds the causal / sequence-end key mask (diagonal chunk
   // and ragged tail only).
-  auto tile_math = [&](auto p_tag, auto m_tag, int kpos0) {
+  auto tile_math = [&](auto p_tag, auto m_tag, int kpos0, bool more) {
     constexpr int P = decltype(p_tag)::value;
     constexpr bool MASKED = decltype(m_tag)::value;
     constexpr int NS = D / 8;                                 // MFMAs per product and tile
@@ -298,6 +299,12 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
 #pragma unroll
       for (int i = 0; i < NS; i++) {
         if (i + KAHEAD < NS) kf[i + KAHEAD] = k_read(i + KAHEAD);
+        // the copies of the next tile are issued one at a time between the MFMAs: a
+        // burst right after the barrier would queue all waves behind the 64 B/clk
+        // global -> LDS path
+        if ((i & 1) == 0 && (i >> 1) < 2 * C::COPIES) {
+          if (more) copy_one(i >> 1, P ^ 1);
+        }
         const int ks = i >> 1, kt = i & 1;
         if (ks == 0) {
           const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -339,7 +346,46 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
     // may reach 2^kLazy, which fp32 / bf16 hold without loss, and the final
     // division by the row sum is unaffected.  Raising it is rare after the
     // first tiles, so the O rescale below is almost never executed.
-    if (__any(tmax > m_run + kLazy)) {
+    // The two outcomes rejoin only after the second product, so the accumulators
+    // never have to be copied between registers on the common path.
+    auto second_product = [&]() {
+      const float off = bias_row - (m_run == -INFINITY ? 0.f : m_run);
+      u32x4 pb[4];
+      float lsum = 0.f;
+      // exponential pair k: P^T slots 2 (k % 4), + 1 of contraction step g = k / 4
+      auto e_pair = [&](int k) {
+        const int g = k >> 2, kt = g >> 1, j = 8 * (g & 1) + 2 * (k & 3);
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, off));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][j + 1], a.c1, off));
+        lsum += p0 + p1;
+        asm volatile("" : "+v"(lsum));   // keeps the row-sum update in its slot
+        const bf16x2 w = {(__bf16)p0, (__bf16)p1};
+        pb[g][k & 3] = __builtin_bit_cast(uint32_t, w);
+      };
+      {
+        bf16x8 vf[NS];
+#pragma unroll
+        for (int i = 0; i < VAHEAD; i++) vf[i] = v_read(i);
+#pragma unroll
+        for (int k = 0; k < 4; k++) e_pair(k);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NS; i++) {
+          if (i + VAHEAD < NS) vf[i + VAHEAD] = v_read(i + VAHEAD);
+          const int g = i / NDT, t = i % NDT;
+          oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], __builtin_bit_cast(bf16x8, pb[g]), oacc[t], 0, 0, 0);
+          // the remaining 12 pairs go behind the first MFMAs: pairs of step g + 1
+          // must be complete before slot NDT * (g + 1)
+          constexpr int PPS = D == 128 ? 1 : 2;
+#pragma unroll
+          for (int kk = 0; kk < PPS; kk++)
+            if (4 + i * PPS + kk < 16) e_pair(4 + i * PPS + kk);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      l_run += lsum;
+    };
+    if (__builtin_expect(__any(tmax > m_run + kLazy), 0)) {
       const float m_new = fmaxf(m_run, tmax);
       const float m_use = m_new == -INFINITY ? 0.f : m_new;
       const float corr = __builtin_amdgcn_exp2f(m_run - m_use);   // m_run = -inf -> 0
@@ -348,55 +394,26 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
 #pragma unroll
       for (int dt = 0; dt < NDT; dt++)
 #pragma unroll
-        for (int j = 0; j < 16; j++)   // in place: the accumulators must not move between registers
-          asm volatile("v_mul_f32 %0, %1, %0" : "+v"(oacc[dt][j]) : "v"(corr));
+        for (int j = 0; j < 16; j++) oacc[dt][j] *= corr;
+      second_product();
+    } else {
+      second_product();
     }
-    const float off = bias_row - (m_run == -INFINITY ? 0.f : m_run);
-    u32x4 pb[4];
-    float lsum = 0.f;
-    // exponential pair k: P^T slots 2 (k % 4), + 1 of contraction step g = k / 4
-    auto e_pair = [&](int k) {
-      const int g = k >> 2, kt = g >> 1, j = 8 * (g & 1) + 2 * (k & 3);
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, off));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][j + 1], a.c1, off));
-      lsum += p0 + p1;
-      asm volatile("" : "+v"(lsum));   // keeps the row-sum update in its slot
-      const bf16x2 w = {(__bf16)p0, (__bf16)p1};
-      pb[g][k & 3] = __builtin_bit_cast(uint32_t, w);
-    };
-    {
-      bf16x8 vf[NS];
-#pragma unroll
-      for (int i = 0; i < VAHEAD; i++) vf[i] = v_read(i);
-#pragma unroll
-      for (int k = 0; k < 4; k++) e_pair(k);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < NS; i++) {
-        if (i + VAHEAD < NS) vf[i + VAHEAD] = v_read(i + VAHEAD);
-        const int g = i / NDT, t = i % NDT;
-        oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], __builtin_bit_cast(bf16x8, pb[g]), oacc[t], 0, 0, 0);
-        // the remaining 12 pairs go behind the first MFMAs: pairs of step g + 1
-        // must be complete before slot NDT * (g + 1)
-        constexpr int PPS = D == 128 ? 1 : 2;
-#pragma unroll
-        for (int kk = 0; kk < PPS; kk++)
-          if (4 + i * PPS + kk < 16) e_pair(4 + i * PPS + kk);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    l_run += lsum;
   };
 
   // ---- main loop -----------------------------------------------------------
   // LDS: K ring [2] then V ring [2]; tile j lives in slot j & 1 of both.  At the
   // top of iteration j the wave waits for its own copies of tile j, the barrier
   // makes everybody's copies visible and guarantees that tile j - 1 (the other
-  // slot) is no longer read; then the copies of tile j + 1 start and run during
-  // the computation of tile j.  The loop body is written out twice so that the
+  // slot) is no longer read; then the copies of tile j + 1 are issued between the
+  // MFMAs of the first product of tile j and run during the rest of it.  The loop body is written out twice so that the
   // slot is a compile-time constant.
   bool have = advance();
-  if (have) { copy_k(it_u, it_sub, 0); copy_v(it_u, it_sub, 0); }
+  if (have) {
+    copy_begin(it_u, it_sub);
+#pragma unroll
+    for (int c = 0; c < 2 * C::COPIES; c++) copy_one(c, 0);
+  }
   auto iteration = [&](auto p_tag) {
     constexpr int P = decltype(p_tag)::value;
     const int cu = it_u, csub = it_sub;
@@ -404,11 +421,14 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's copies of tile j have landed
     __syncthreads();
     if (csub == 0) begin_chunk(cu);
-    if (more) { copy_k(it_u, it_sub, P ^ 1); copy_v(it_u, it_sub, P ^ 1); }
+    if (more) copy_begin(it_u, it_sub);
     if (wave_on) {
       const int kpos0 = cu * a.block + csub * 64;
-      if (diag || kpos0 + 64 > a.n_kv) tile_math(p_tag, std::true_type{}, kpos0);
-      else tile_math(p_tag, std::false_type{}, kpos0);
+      if (diag || kpos0 + 64 > a.n_kv) tile_math(p_tag, std::true_type{}, kpos0, more);
+      else tile_math(p_tag, std::false_type{}, kpos0, more);
+    } else if (more) {
+#pragma unroll
+      for (int c = 0; c < 2 * C::COPIES; c++) copy_one(c, P ^ 1);
     }
     have = more;
   };
