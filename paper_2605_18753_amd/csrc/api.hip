@@ -54,7 +54,7 @@ int make_layout(const dash_params* p, Layout* L, bool routing) {
     const char* env = getenv("DASH_DECODE_WGS");   // tuning aid: target workgroup count
     const int target = env ? atoi(env) : 512;
     splits = (target + pairs - 1) / pairs;
-    if (splits > 32) splits = 32;
+    if (splits > 64) splits = 64;
     if (splits > L->t_all) splits = L->t_all;
     if (splits < 1) splits = 1;
   }
