@@ -30,7 +30,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the Stage-2 kernel on the full C2 workload, from the two
 # rocprofv3 --pmc runs summarised in profiles/bench_c2_c3_hbm_traffic.md
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0).  Not measurable from inside this script.
-S2_TRAFFIC_BYTES_C2 = 2.396e9 + 0.268e9
+S2_TRAFFIC_BYTES_C2 = 2.539e9 + 0.388e9
 
 
 def parse():
@@ -157,6 +157,23 @@ def bench_decode(w, steps, warmup, torch, B, make_inputs):
     return res
 
 
+def gemm_context(torch):
+    """Library bf16 GEMM rate (8192^3, hipBLASLt through torch) with N(0,1) and with
+    all-zero operands: how far the chip's power management lets dense bf16 MFMA
+    work run on data that toggles, as context for the MFMA roofline fraction."""
+    n = 8192
+    out = {}
+    for name in ("normal", "zeros"):
+        a = torch.randn(n, n, device="cuda:0", dtype=torch.bfloat16) if name == "normal" else \
+            torch.zeros(n, n, device="cuda:0", dtype=torch.bfloat16)
+        b = a.t().contiguous()
+        ms = timed(lambda: torch.mm(a, b), 10, 3, torch)
+        out[name] = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
+        del a, b
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(w, seconds, torch, make_inputs):
     """The oracle as it stands, single thread, on a uniform sample of query rows of
     the same workload; reported in the metric's unit (dense-equivalent flops / s)."""
@@ -221,6 +238,7 @@ def main():
         dec = dict(gamma1=bench_decode(wd, max(a.steps, 20), a.warmup, torch, B, make_inputs),
                    gamma04=bench_decode(wd.replace(gamma=0.4), max(a.steps, 20), a.warmup, torch, B, make_inputs))
     cpu = None if a.no_cpu else cpu_baseline(w, a.cpu_seconds, torch, make_inputs)
+    gemm = None if a.small else gemm_context(torch)
 
     def tf(flops, ms):
         return flops / (ms * 1e-3) / 1e12
@@ -236,7 +254,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "h_q": w.h_q, "h_kv": w.h_kv, "n": w.n_q,
                    "head_dim": w.head_dim, "block": w.block, "alpha": w.alpha, "gamma": w.gamma,
                    "sigma": w.sigma, "causal": True, "offset_sigma": w.offset_sigma, "seed": w.seed},
-        "roofline": {"bound": "mfma", "kernel": "s2_attend_kernel<128,1,false,false>",
+        "roofline": {"bound": "mfma", "kernel": "s2_attend_kernel<128,false>",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": None if a.small else S2_TRAFFIC_BYTES_C2},
@@ -251,6 +269,7 @@ def main():
             "stage2_exec_tflops": tf(main_res["f_exec"], main_res["ms_stage2"]),
             "stage2_exec_mfma_frac": tf(main_res["f_exec"], main_res["ms_stage2"]) / MFMA_BF16_PEAK_TFLOPS,
             "f_alg_over_f_exec": main_res["f_alg"] / main_res["f_exec"],
+            "library_gemm_bf16_tflops": gemm,
             "at_75pct_sparsity": {
                 "gamma": w75.gamma, "chunk_sparsity": res75["sparsity"],
                 "effective_tflops": tf(res75["f_dense"], res75["ms_step"]),

@@ -35,15 +35,11 @@
 
 #include "common.h"
 #include "dash_internal.h"
+#include "lds_copy.h"
 #include "stage2_args.h"
 
 namespace dash {
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
 
 template <int D> struct S2Cfg {
   static constexpr int NCH = D / 8;                       // 16-byte chunks per row
@@ -65,29 +61,6 @@ template <int D> __device__ __forceinline__ int k_swz(int row) {
 }
 template <int D> __device__ __forceinline__ int v_swz(int row) {
   return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
-}
-
-// Buffer resource (raw, no stride) over `bytes` bytes at p: loads past the end
-// return zero instead of touching memory.
-__device__ __forceinline__ u32x4 make_rsrc(const void* p, int64_t bytes) {
-  const uint64_t base = (uint64_t)p;
-  u32x4 rs;
-  rs[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
-  rs[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
-  rs[2] = __builtin_amdgcn_readfirstlane((uint32_t)bytes);
-  rs[3] = 0x00020000u;
-  return rs;
-}
-
-// One wave copies 64 x 16 bytes from global memory straight into LDS: lane l
-// fetches 16 bytes at resource base + voff (per lane) + soff (uniform) and they
-// land at LDS byte address lds_addr (uniform) + 16 l.  The copy is counted by
-// vmcnt; it is issued from assembly so that the compiler does not order later
-// LDS reads of the other slots behind it, and the caller waits with
-// s_waitcnt vmcnt(0) before the barrier that publishes the slot.
-__device__ __forceinline__ void copy16_to_lds(u32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 
 template <int D, bool DENSE>
@@ -195,7 +168,7 @@ __global__ __launch_bounds__(256, 2) void s2_attend_kernel(S2Args a) {
   // last tile has beyond n_kv read as zeros instead of touching memory.
   const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
   const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  const uint32_t lds0 = lds_addr_of(lds);
   const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
   const uint32_t k_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ k_swz<D>(c_row)) << 4));
   const uint32_t v_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ v_swz<D>(c_row)) << 4));

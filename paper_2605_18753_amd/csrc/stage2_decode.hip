@@ -25,13 +25,11 @@
 
 #include "common.h"
 #include "dash_internal.h"
+#include "lds_copy.h"
 #include "stage2_args.h"
 
 namespace dash {
 
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kDecStages = 3;   // LDS ring depth (sub-tiles)
 
@@ -51,21 +49,6 @@ template <int D> __device__ __forceinline__ int dk_swz(int row) {
 }
 template <int D> __device__ __forceinline__ int dv_swz(int row) {
   return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
-}
-
-__device__ __forceinline__ u32x4 dec_rsrc(const void* p, int64_t bytes) {
-  const uint64_t base = (uint64_t)p;
-  u32x4 rs;
-  rs[0] = __builtin_amdgcn_readfirstlane((uint32_t)base);
-  rs[1] = __builtin_amdgcn_readfirstlane((uint32_t)(base >> 32) & 0xffffu);
-  rs[2] = __builtin_amdgcn_readfirstlane((uint32_t)bytes);
-  rs[3] = 0x00020000u;
-  return rs;
-}
-// 64 x 16 bytes global -> LDS (see copy16_to_lds in stage2.hip)
-__device__ __forceinline__ void dec_copy16(u32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 
 template <int D, bool DENSE>
@@ -146,9 +129,9 @@ __global__ __launch_bounds__(256, 3) void s2_decode_kernel(S2Args a) {
   }
 
   // ---- global -> LDS sub-tile copies (layout as in the prefill kernel) -------
-  const u32x4 k_rs = dec_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
-  const u32x4 v_rs = dec_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds;
+  const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
+  const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
+  const uint32_t lds0 = lds_addr_of(lds);
   const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
   const uint32_t k_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ dk_swz<D>(c_row)) << 4));
   const uint32_t v_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ dv_swz<D>(c_row)) << 4));
@@ -161,9 +144,9 @@ __global__ __launch_bounds__(256, 3) void s2_decode_kernel(S2Args a) {
     const uint32_t key0 = (uint32_t)(cp_id * a.block + cp_sub * 32);
     const uint32_t tk = key0 * (uint32_t)a.ks_t * 2u, tv = key0 * (uint32_t)a.vs_t * 2u;
 #pragma unroll
-    for (int i = 0; i < C::COPIES; i++) dec_copy16(k_rs, dst + i * 4096, k_off, tk + i * k_step);
+    for (int i = 0; i < C::COPIES; i++) copy16_to_lds(k_rs, dst + i * 4096, k_off, tk + i * k_step);
 #pragma unroll
-    for (int i = 0; i < C::COPIES; i++) dec_copy16(v_rs, dst + C::SUB_BYTES + i * 4096, v_off, tv + i * v_step);
+    for (int i = 0; i < C::COPIES; i++) copy16_to_lds(v_rs, dst + C::SUB_BYTES + i * 4096, v_off, tv + i * v_step);
     cp_t++;
     if (++cp_sub == nsub) { cp_sub = 0; if (it_e < e1) cp_id = next_id(); }
   };
