@@ -6,7 +6,7 @@ import torch
 
 from oracle import dash_oracle as orc
 from paper_2605_18753_amd import binding as B
-from paper_2605_18753_amd.inputs import C1, C2, C3, C5, Workload, make_inputs, shrink
+from paper_2605_18753_amd.inputs import C1, C2, C3, C4, C5, Workload, make_inputs, shrink
 
 import parity_util as U
 
@@ -178,6 +178,19 @@ def test_prefill_c2_full_size_sampled():
     run = U.run_prefill(w, q, k, v, want_idx=False)
     rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96, heads=[(0, 0), (0, 5), (0, 7)]))
     print(f"C2 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+
+
+@pytest.mark.parametrize("alpha,offset_sigma", [(1.5, 0.5), (2.0, 1.0), (1.25, 1.0)])
+def test_prefill_c4_full_size_sampled(alpha, offset_sigma):
+    """Long prefill (N = 131072, chunks of 128 keys) at three points of the alpha / offset sweep."""
+    w = C4.replace(alpha=alpha, offset_sigma=offset_sigma)
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 48, heads=[(0, 1), (0, 6)]))
+    print(f"C4 alpha={alpha} offset_sigma={offset_sigma}: rows {rep.rows} sparsity {rep.sparsity:.3f} "
+          f"exempt {rep.exempt} out_err {err:.2e}")
+    del run, q, k, v
+    torch.cuda.empty_cache()
 
 
 def test_prefill_c5_full_size_sampled():
