@@ -42,6 +42,10 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--small", action="store_true", help="shrunken shapes (debugging)")
+    ap.add_argument("--paper-protocol", action="store_true",
+                    help="run the kernel-benchmark protocol of the paper instead (H_q=32, H_kv=2, d=128, chunk 64, "
+                         "N in 16K..96K, Stage-2 mask randomised to 75 / 87.5 / 93.75 % sparsity, speed-up over the "
+                         "in-library dense kernel; prefill batch 1, decode batch 24) and print its JSON line")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy three times (known traffic, to scale the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -157,6 +161,74 @@ def bench_decode(w, steps, warmup, torch, B, make_inputs):
     return res
 
 
+def paper_protocol(steps, warmup, torch, B):
+    """Stage-2 speed-up over the in-library dense attention on the shapes and the
+    randomised masks of the paper's kernel benchmark (Sec. 5.3, App. B.3, Table 5).
+    Stage 0/1 do not depend on the mask; their time on the same tensors is given
+    beside it so that the speed-up can be read with and without routing."""
+    from paper_2605_18753_amd.inputs import random_chunk_lists
+    dev = "cuda:0"
+    h_q, h_kv, d, blk = 32, 2, 128, 64
+    sparsities = (0.75, 0.875, 0.9375)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    out = {"shape": {"h_q": h_q, "h_kv": h_kv, "head_dim": d, "block": blk, "dtype": "bf16"},
+           "prefill_batch": 1, "decode_batch": 24, "prefill": {}, "decode": {}}
+    for n in (16384, 32768, 65536, 98304):
+        # ---- prefill, batch 1
+        q = torch.randn((1, h_q, n, d), generator=gen, device=dev).bfloat16()
+        k = torch.randn((1, h_kv, n, d), generator=gen, device=dev).bfloat16()
+        v = torch.randn((1, h_kv, n, d), generator=gen, device=dev).bfloat16()
+        o = torch.empty_like(q)
+        p = B.make_params(q, k, v, o, blk)
+        ws = B.alloc_workspace(p, dev)
+        kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
+        t_dense = timed(lambda: B.dense_attn(p, q, k, v, o, ws), steps, warmup, torch)
+        lists = B.Lists.allocate(p, dev, idx=False, tau=False)
+        t_s0 = timed(lambda: B.dash_kbar_compress(p, k, kbar), steps, 1, torch)
+        t_s1 = timed(lambda: B.dash_stage1_route(p, q, kbar, lists, ws), steps, 1, torch)
+        del lists
+        row = {"dense_ms": t_dense, "stage0_ms": t_s0, "stage1_ms": t_s1}
+        for s_ in sparsities:
+            mask, cnt, bias = random_chunk_lists(1, h_kv, n, n, blk, s_, dev, seed=1)
+            ls = B.Lists(mask=mask, bias=bias)
+            t_s2 = timed(lambda: B.dash_stage2_attend(p, q, k, v, o, ls, ws), steps, warmup, torch)
+            row[f"s{s_}"] = {"stage2_ms": t_s2, "speedup_stage2": t_dense / t_s2,
+                             "speedup_with_routing": t_dense / (t_s0 + t_s1 + t_s2)}
+            del mask, cnt, bias, ls
+        out["prefill"][str(n)] = row
+        del q, k, v, o, ws, kbar
+        torch.cuda.empty_cache()
+        # ---- decode, batch 24
+        bd = 24
+        q = torch.randn((bd, h_q, 1, d), generator=gen, device=dev).bfloat16()
+        k = torch.randn((bd, h_kv, n, d), generator=gen, device=dev).bfloat16()
+        v = torch.randn((bd, h_kv, n, d), generator=gen, device=dev).bfloat16()
+        o = torch.empty_like(q)
+        p = B.make_params(q, k, v, o, blk)
+        ws = B.alloc_workspace(p, dev)
+        kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
+        B.dash_kbar_compress(p, k, kbar)
+        t_dense = timed(lambda: B.dense_attn(p, q, k, v, o, ws), max(steps, 20), warmup, torch)
+        lists = B.Lists.allocate(p, dev, idx=False, tau=False)
+        t_s1 = timed(lambda: B.dash_stage1_route(p, q, kbar, lists, ws), max(steps, 20), 1, torch)
+        del lists
+        row = {"dense_us": t_dense * 1e3, "stage1_us": t_s1 * 1e3}
+        for s_ in sparsities:
+            mask, cnt, bias = random_chunk_lists(bd, h_kv, 1, n, blk, s_, dev, seed=2)
+            ls = B.Lists(mask=mask, bias=bias)
+            t_s2 = timed(lambda: B.dash_stage2_attend(p, q, k, v, o, ls, ws), max(steps, 20), warmup, torch)
+            kv_bytes = float(cnt.sum()) * blk * d * 2 * 2
+            row[f"s{s_}"] = {"stage2_us": t_s2 * 1e3, "speedup_stage2": t_dense / t_s2,
+                             "speedup_with_routing": t_dense / (t_s1 + t_s2),
+                             "kv_GBps_stage2": kv_bytes / (t_s2 * 1e-3) / 1e9}
+            del mask, cnt, bias, ls
+        out["decode"][str(n)] = row
+        del q, k, v, o, ws, kbar
+        torch.cuda.empty_cache()
+    return out
+
+
 def gemm_context(torch):
     """Library bf16 GEMM rate (8192^3, hipBLASLt through torch) with N(0,1) and with
     all-zero operands: how far the chip's power management lets dense bf16 MFMA
@@ -221,6 +293,12 @@ def main():
         w = w.replace(n_q=4096, n_kv=4096, name="C2_small")
         wd = wd.replace(n_kv=16384, batch=4, name="C3_small")
 
+    if a.paper_protocol:
+        res = paper_protocol(a.steps, a.warmup, torch, B)
+        print(json.dumps({"metric": "Stage-2 speed-up over the in-library dense attention, randomised chunk masks "
+                                    "(kernel-benchmark protocol of the paper)", "unit": "x", "n_gpus": 1,
+                          "data": "synthetic", "dtype": "bf16", **res}))
+        return
     if a.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)

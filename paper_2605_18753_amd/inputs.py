@@ -143,3 +143,37 @@ def shrink(w: Workload, *, n: Optional[int] = None, batch: Optional[int] = None,
         kw["h_kv"] = h_kv
     kw["name"] = name or (w.name + "_small")
     return w.replace(**kw)
+
+
+def random_chunk_lists(batch: int, h_kv: int, n_q: int, n_kv: int, block: int, sparsity: float,
+                       device="cpu", seed: int = 0, bias_sigma: float = 0.0):
+    """Randomised attended-chunk lists in the Stage-1 output format, the stand-in
+    for the kernel benchmark of the paper (App. B.3: the Stage-2 block mask is
+    randomised to a target sparsity).  Query t sits at position n_kv - n_q + t;
+    every complete chunk before its own is kept independently with probability
+    1 - sparsity, its own (diagonal) chunk always.  Returns (mask int32
+    [batch,h_kv,n_q,words], cnt int32 [batch,h_kv,n_q], bias fp32
+    [batch,h_kv,n_q,t_all]): bias holds N(0, bias_sigma^2) draws for the kept
+    chunks in ascending chunk order and 0 for the diagonal chunk, which comes last.
+    """
+    gen = _gen(device, seed)
+    t_all = (n_kv + block - 1) // block
+    words = (t_all + 31) // 32
+    pos = torch.arange(n_q, device=device) + (n_kv - n_q)
+    c_i = (pos // block).view(1, 1, n_q, 1)
+    c = torch.arange(words * 32, device=device).view(1, 1, 1, -1)
+    keep = torch.rand((batch, h_kv, n_q, words * 32), generator=gen, device=device) >= sparsity
+    bits = (keep & (c < c_i)) | (c == c_i)
+    cnt = bits.sum(-1).to(torch.int32)
+    shifts = torch.arange(32, device=device, dtype=torch.int64)
+    packed = (bits.view(batch, h_kv, n_q, words, 32).to(torch.int64) << shifts).sum(-1)
+    mask = torch.where(packed >= 2 ** 31, packed - 2 ** 32, packed).to(torch.int32)
+    bias = torch.zeros((batch, h_kv, n_q, t_all), dtype=torch.float32, device=device)
+    if bias_sigma > 0.0:
+        dense = torch.randn((batch, h_kv, n_q, words * 32), generator=gen, device=device) * bias_sigma
+        dense = torch.where(c == c_i, torch.zeros_like(dense), dense)
+        order = torch.argsort((~bits).to(torch.int8), dim=-1, stable=True)     # kept chunks first, ascending
+        bias = torch.gather(dense, -1, order)[..., :t_all].contiguous()
+        rank = torch.arange(t_all, device=device).view(1, 1, 1, -1)
+        bias = torch.where(rank < cnt.unsqueeze(-1), bias, torch.zeros_like(bias))
+    return mask, cnt, bias

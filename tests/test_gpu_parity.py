@@ -6,7 +6,7 @@ import torch
 
 from oracle import dash_oracle as orc
 from paper_2605_18753_amd import binding as B
-from paper_2605_18753_amd.inputs import C1, C2, C3, C4, C5, Workload, make_inputs, shrink
+from paper_2605_18753_amd.inputs import C1, C2, C3, C4, C5, Workload, make_inputs, random_chunk_lists, shrink
 
 import parity_util as U
 
@@ -212,3 +212,54 @@ def test_decode_c3_full_size_sampled():
     cnt = run.lists.cnt.cpu().numpy()
     assert cnt.min() >= 1 and cnt.max() <= 2048
     assert torch.isfinite(run.o.float()).all()
+
+
+# ---- Stage 2 on given lists (the kernel-benchmark protocol: randomised masks) ----
+def _check_given_lists(w, q, k, v, o, mask, cnt, bias, rows):
+    qn, kn, vn = U.to_np(q), U.to_np(k), U.to_np(v)
+    on = U.to_np(o)
+    g = w.h_q // w.h_kv
+    scale = 1.0 / np.sqrt(w.head_dim)
+    mk = mask.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+    worst = 0.0
+    for (b, r, i) in rows:
+        pos = w.n_kv - w.n_q + i
+        c_i = pos // w.block
+        ids = [c for c in range(c_i) if (mk[b, r, i, c >> 5] >> (c & 31)) & 1]
+        assert len(ids) + 1 == int(cnt[b, r, i])
+        bs = bias[b, r, i, :len(ids)].cpu().numpy().astype(np.float64)
+        ref = orc.attend_bias_form(qn[b, r * g:(r + 1) * g, i], kn[b, r], vn[b, r], scale, w.block,
+                                   np.asarray(ids, dtype=np.int64), bs, c_i * w.block, pos + 1)
+        worst = max(worst, np.abs(on[b, r * g:(r + 1) * g, i] - ref).max() / np.abs(ref).max())
+    return worst
+
+
+@pytest.mark.parametrize("g_q,n,block,sparsity", [(16, 2048, 64, 0.75), (16, 1500, 64, 0.9375), (4, 2048, 128, 0.875)])
+def test_stage2_given_random_lists_prefill(g_q, n, block, sparsity):
+    w = Workload("given_lists", 1, 2 * g_q, 2, n, n, 128, block, seed=21)
+    q, k, v = gen(w)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, block)
+    mask, cnt, bias = random_chunk_lists(1, 2, n, n, block, sparsity, DEV, seed=5, bias_sigma=1.0)
+    ws = B.alloc_workspace(p, DEV)
+    B.dash_stage2_attend(p, q, k, v, o, B.Lists(mask=mask, bias=bias), ws)
+    torch.cuda.synchronize()
+    rows = [(0, r, i) for r in (0, 1) for i in (0, 1, block - 1, block, n // 2, n - 2, n - 1, 777 % n, 1234 % n)]
+    worst = _check_given_lists(w, q, k, v, o, mask, cnt, bias, rows)
+    print(f"given lists g_q={g_q} n={n} sparsity={sparsity}: out_err {worst:.2e}")
+    assert worst <= 2e-2
+
+
+def test_stage2_given_random_lists_decode():
+    w = Workload("given_lists_decode", 3, 32, 2, 1, 5000, 128, 64, seed=22)
+    q, k, v = gen(w)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, 64)
+    mask, cnt, bias = random_chunk_lists(3, 2, 1, 5000, 64, 0.75, DEV, seed=6, bias_sigma=1.0)
+    ws = B.alloc_workspace(p, DEV)
+    B.dash_stage2_attend(p, q, k, v, o, B.Lists(mask=mask, bias=bias), ws)
+    torch.cuda.synchronize()
+    rows = [(b, r, 0) for b in range(3) for r in range(2)]
+    worst = _check_given_lists(w, q, k, v, o, mask, cnt, bias, rows)
+    print(f"given lists decode: out_err {worst:.2e}")
+    assert worst <= 2e-2
