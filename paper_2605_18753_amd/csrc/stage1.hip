@@ -34,7 +34,7 @@ struct S1Args {
   int32_t* idx;
   float* bias;
   float* tau;
-  int h_q, h_kv, g_q, n_q, block, t_c, t_all, words, pos0, causal, ld;
+  int batch, h_q, h_kv, g_q, n_q, block, t_c, t_all, words, pos0, causal, ld;
   int64_t qs_b, qs_h, qs_t;
   float xscale, pexp, alpha, inv_sigma;
 };
@@ -341,8 +341,12 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
   __shared__ uint32_t mwords[4][64];
   constexpr int ROWS = 16 * MT;
   const int tokt = ROWS / a.g_q;
-  const int tile = gridDim.x - 1 - blockIdx.x;   // longest rows first
-  const int r = blockIdx.y, b = blockIdx.z;
+  // workgroup id -> (tile, kv-head, batch), the (head, batch) pair fastest: the 8
+  // XCDs are fed round robin, so each one keeps few heads' summaries in its L2
+  const int hb = a.h_kv * a.batch;
+  const int hbi = blockIdx.x % hb;
+  const int tile = (int)(gridDim.x / hb) - 1 - (int)(blockIdx.x / hb);   // longest rows first
+  const int r = hbi % a.h_kv, b = hbi / a.h_kv;
   const int tok0 = tile * tokt;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   int n_cand = a.causal ? (a.pos0 + tok0) / a.block : a.t_c;
@@ -364,17 +368,43 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
       }
       const int ntile_c = (n_cand + 15) >> 4;
       const uint16_t* kb = a.ksplit + ((int64_t)b * a.h_kv + r) * a.t_c * 3 * D + kq * 8;
-      // operand registers are double buffered: the loads of this wave's next chunk
-      // tile are in flight while the current one goes through the MFMAs
-      bf16x8 kf[2][3][D / 32];
-      auto load_tile = [&](int ct, bf16x8 (&dst)[3][D / 32]) {
+      // Operand registers are double buffered: the loads of this wave's next chunk
+      // tile are in flight while the current one goes through the MFMAs.  The loads
+      // are issued from assembly and waited for by count (the newest tile's loads may
+      // stay outstanding): left to the compiler, the schedule ends up waiting for the
+      // loads it has just issued, which exposes the L2 latency once per tile.
+      constexpr int KS = D / 32;
+      bf16x8 kf[2][3][KS];
+      auto load_tile = [&](int ct, bf16x8 (&dst)[3][KS]) {
         const int c = ct * 16 + m;
         const uint16_t* kp = kb + (int64_t)(c < n_cand ? c : n_cand - 1) * 3 * D;
 #pragma unroll
         for (int sp = 0; sp < 3; sp++)
 #pragma unroll
-          for (int ks = 0; ks < D / 32; ks++)
-            dst[sp][ks] = *reinterpret_cast<const bf16x8*>(kp + sp * D + ks * 32);
+          for (int ks = 0; ks < KS; ks++)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2"
+                         : "=v"(dst[sp][ks]) : "v"(kp), "n"((sp * D + ks * 32) * 2) : "memory");
+      };
+      // wait until at most `newer` loads are outstanding; the fragments are passed
+      // through so that their consumers cannot be scheduled above the wait
+      auto wait_tile = [&](bf16x8 (&t)[3][KS], bool next_in_flight) {
+        if (next_in_flight) {
+          if constexpr (KS == 4)
+            asm volatile("s_waitcnt vmcnt(12)" : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[0][2]), "+v"(t[0][3]),
+                         "+v"(t[1][0]), "+v"(t[1][1]), "+v"(t[1][2]), "+v"(t[1][3]),
+                         "+v"(t[2][0]), "+v"(t[2][1]), "+v"(t[2][2]), "+v"(t[2][3]));
+          else
+            asm volatile("s_waitcnt vmcnt(6)" : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[1][0]), "+v"(t[1][1]),
+                         "+v"(t[2][0]), "+v"(t[2][1]));
+        } else {
+          if constexpr (KS == 4)
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[0][2]), "+v"(t[0][3]),
+                         "+v"(t[1][0]), "+v"(t[1][1]), "+v"(t[1][2]), "+v"(t[1][3]),
+                         "+v"(t[2][0]), "+v"(t[2][1]), "+v"(t[2][2]), "+v"(t[2][3]));
+          else
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(t[0][0]), "+v"(t[0][1]), "+v"(t[1][0]), "+v"(t[1][1]),
+                         "+v"(t[2][0]), "+v"(t[2][1]));
+        }
       };
       auto mma_tile = [&](int ct, const bf16x8 (&src)[3][D / 32]) {
         f32x4 acc_hi[MT], acc_lo[MT];
@@ -397,12 +427,21 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
               S[(mt * 16 + 4 * kq + j) * a.ld + c] = (acc_hi[mt][j] + acc_lo[mt][j]) * a.xscale;
         }
       };
+      // the Q fragments must have landed (and be known to) before the counted waits
+#pragma unroll
+      for (int mt = 0; mt < MT; mt++)
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) asm volatile("" : "+v"(qf[mt][ks]));
       if (wave < ntile_c) load_tile(wave, kf[0]);
       for (int ct = wave; ct < ntile_c; ct += 8) {
-        if (ct + 4 < ntile_c) load_tile(ct + 4, kf[1]);
+        const bool more1 = ct + 4 < ntile_c;
+        if (more1) load_tile(ct + 4, kf[1]);
+        wait_tile(kf[0], more1);
         mma_tile(ct, kf[0]);
-        if (ct + 4 < ntile_c) {
-          if (ct + 8 < ntile_c) load_tile(ct + 8, kf[0]);
+        if (more1) {
+          const bool more2 = ct + 8 < ntile_c;
+          if (more2) load_tile(ct + 8, kf[0]);
+          wait_tile(kf[1], more2);
           mma_tile(ct + 4, kf[1]);
         }
       }
@@ -582,7 +621,7 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
   S1Args a;
   a.q = q; a.ksplit = ksplit; a.scores = scores;
   a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
-  a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.block = p.block_size;
+  a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.block = p.block_size;
   a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal;
   a.ld = ((L.t_c + 15) / 16) * 16 + 4;
   a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
@@ -594,7 +633,8 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
     else if ((size_t)32 * a.ld * 4 <= 81920) mt = 2;
   }
   const int tokt = 16 * mt / L.g_q;
-  dim3 grid((p.n_q + tokt - 1) / tokt, p.h_kv, p.batch);
+  // x = tiles * kv-heads * batch, decoded in the kernel
+  dim3 grid((unsigned)(((p.n_q + tokt - 1) / tokt) * p.h_kv * p.batch), 1, 1);
   const size_t lds = (size_t)16 * mt * a.ld * 4;
   if (!mfma) {
     if (p.head_dim == 128) return launch_route_k(s1_route_kernel<1, 128, false>, a, grid, lds, st);
