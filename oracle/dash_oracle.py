@@ -10,6 +10,8 @@ What each function follows (paper sections / equations / algorithms):
 
   block_mean_summaries   Stage 0, Eq. 3 with the summary query at its zero
                          initial value (uniform mean pooling), Alg. 1
+  local_attention_summaries
+                         Stage 0 with a learned summary query, Eq. 3 / Alg. 1
   entmax_threshold_*     Eq. 2 / App. A Eq. 11: tau with sum_i [x_i-tau]_+^(1/(a-1)) = 1
   entmax                 Eq. 2
   route_token            Stage 1, Eq. 4 and the GQA averaging paragraph; Alg. 2
@@ -25,7 +27,9 @@ Pins (tests/test_oracle_*.py, all CPU): entmax closed forms, simplex
 invariants, alpha=2 == Euclidean projection, alpha->1 == softmax, brute force
 over supports on tiny inputs, exact-vs-bisection agreement, Proposition 1
 (literal form == bias form), sigma->inf == masked softmax, gamma->0 == dense
-causal attention, block-permutation invariance.
+causal attention, block-permutation invariance; learned summaries: zero query
+== block mean (bit for bit), a library softmax + matmul per chunk, the
+argmax-key limit, convex-hull bounds, shift equivariance.
 
 Parity unpinned: the paper prints no worked numerical example, so absolute
 output values at finite sigma are pinned only through Proposition 1 and the
@@ -42,7 +46,7 @@ from typing import Iterable, List, Optional, Sequence, Tuple
 import numpy as np
 
 __all__ = [
-    "block_mean_summaries", "entmax_threshold_exact", "entmax_threshold_bisect",
+    "block_mean_summaries", "local_attention_summaries", "entmax_threshold_exact", "entmax_threshold_bisect",
     "entmax_threshold", "entmax", "route_token", "prior_bias",
     "attend_bias_form", "prior_literal", "attend_literal", "dense_attention",
     "DashParams", "RowResult", "dash_row_at", "dash_row", "dash_rows", "dash_forward_full",
@@ -64,6 +68,34 @@ def block_mean_summaries(k: np.ndarray, block: int) -> np.ndarray:
     body = k[..., : t_c * block, :].reshape(k.shape[:-2] + (t_c, block, d))
     mean = body.sum(axis=-2) / float(block)
     return mean.astype(np.float32).astype(np.float64)
+
+
+def local_attention_summaries(k: np.ndarray, qbar: np.ndarray, block: int,
+                              scale: Optional[float] = None) -> np.ndarray:
+    """Stage 0 with a learned summary query (Eq. 3; Alg. 1): every complete
+    chunk is summarised by one softmax attention of the summary query over the
+    chunk's own keys, the keys serving as values as well.
+
+    k: [..., h_kv, n, d]; qbar: broadcastable to [..., h_kv, T_c, d] (one vector
+    per kv-head as in Sec. 3.1, or one per chunk as in Alg. 1, where the
+    rotary embedding has been applied to it); scale defaults to 1/sqrt(d).
+    Returns [..., h_kv, T_c, d] as fp64 values exactly representable in fp32
+    (the summary cache is fp32).
+    """
+    k = np.asarray(k, dtype=np.float64)
+    n, d = k.shape[-2], k.shape[-1]
+    t_c = n // block
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    body = k[..., : t_c * block, :].reshape(k.shape[:-2] + (t_c, block, d))
+    qb = np.broadcast_to(np.asarray(qbar, dtype=np.float64), body.shape[:-2] + (d,))
+    out = np.empty(body.shape[:-2] + (d,), dtype=np.float64)
+    for idx in np.ndindex(*body.shape[:-2]):
+        keys = body[idx]                      # [block, d]
+        s = keys @ qb[idx] * scale            # s_t = <qbar, k_t> / sqrt(d)
+        e = np.exp(s - s.max())
+        out[idx] = (e / e.sum()) @ keys       # softmax(s)^T K_c
+    return out.astype(np.float32).astype(np.float64)
 
 
 # --------------------------------------------------------------------------

@@ -199,3 +199,68 @@ def test_routing_is_sparse_and_query_dependent_on_the_recipe():
     sizes = {rr.routed.size for rr in res}
     assert len(sizes) > 3                          # variable number of kept blocks
     assert all(rr.routed.size < rr.n_cand for rr in res)
+
+
+# --------------------------------------------------------------------------
+# Stage 0 with a learned summary query (Eq. 3; Alg. 1)
+# --------------------------------------------------------------------------
+def _bf16_round(x):
+    """Round fp64/fp32 values to bf16 (round to nearest even) and return fp64."""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def test_learned_summary_zero_query_is_block_mean_bit_for_bit():
+    # Sec. 3.1: at initialisation the inner products are zero and the local softmax is uniform pooling
+    rng = np.random.default_rng(11)
+    k = _bf16_round(rng.standard_normal((2, 3, 200, 16)))
+    a = orc.local_attention_summaries(k, np.zeros((3, 1, 16)), 64)
+    b = orc.block_mean_summaries(k, 64)
+    assert a.shape == (2, 3, 3, 16)
+    assert np.array_equal(a, b)
+
+
+def test_learned_summary_equals_library_softmax_attention_per_chunk():
+    # Eq. 3 is one SDPA of the summary query over the chunk, keys as values: a library softmax and a matmul
+    from scipy.special import softmax
+    rng = np.random.default_rng(12)
+    k = rng.standard_normal((2, 130, 8))
+    qbar = rng.standard_normal((2, 2, 8)) * 2.0          # [h_kv, T_c, d]: one query per chunk (Alg. 1)
+    got = orc.local_attention_summaries(k, qbar, 64)
+    for r in range(2):
+        for c in range(2):
+            keys = k[r, c * 64:(c + 1) * 64]
+            w = softmax(keys @ qbar[r, c] / np.sqrt(8.0))
+            ref = (w[None, :] @ keys)[0]
+            assert np.allclose(got[r, c], ref, rtol=0, atol=1e-6)   # fp32 rounding of the cache
+    # a transposed operand or a sum over the wrong axis would break the shape or this value
+    assert got.shape == (2, 2, 8)
+
+
+def test_learned_summary_sharp_query_selects_the_best_matching_key():
+    rng = np.random.default_rng(13)
+    k = rng.standard_normal((1, 64, 8))
+    t_star = 17
+    qbar = 400.0 * k[0, t_star]                          # overwhelming weight on one key
+    s = k[0] @ qbar
+    assert int(np.argmax(s)) == t_star
+    got = orc.local_attention_summaries(k, qbar[None, None, :], 64)
+    assert np.allclose(got[0, 0], k[0, t_star].astype(np.float32), atol=1e-6)
+
+
+def test_learned_summary_is_a_convex_combination_and_shift_equivariant():
+    rng = np.random.default_rng(14)
+    k = rng.standard_normal((3, 128, 8))
+    qbar = rng.standard_normal((3, 1, 8))
+    got = orc.local_attention_summaries(k, qbar, 32)
+    body = k.reshape(3, 4, 32, 8)
+    assert np.all(got <= body.max(axis=2) + 1e-6) and np.all(got >= body.min(axis=2) - 1e-6)
+    # adding one vector u to every key shifts all scores of a chunk by <qbar,u>/sqrt(d), which the
+    # softmax ignores, and shifts the summary by u
+    u = rng.standard_normal(8)
+    got2 = orc.local_attention_summaries(k + u, qbar, 32)
+    assert np.allclose(got2, got + u, atol=2e-6)
+    # the scale multiplies the logits: scale 0 is uniform pooling whatever the query
+    got0 = orc.local_attention_summaries(k, qbar, 32, scale=0.0)
+    assert np.allclose(got0, body.mean(axis=2), atol=1e-6)
