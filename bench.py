@@ -120,12 +120,16 @@ def bench_prefill(w, steps, warmup, torch, B, make_inputs):
     st = prefill_stats(w, lists, torch)
     t_all = timed(lambda: B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws), steps, warmup, torch)
     t_s0 = timed(lambda: B.dash_kbar_compress(p, k, kbar), steps, 1, torch)
+    # Stage 0 in its learned form (one summary query per kv-head), timed beside the block mean
+    qbar = torch.randn((w.h_kv, w.head_dim), dtype=torch.float32, device=dev)
+    kbar_l = torch.empty_like(kbar)
+    t_s0l = timed(lambda: B.dash_kbar_summarize(p, k, qbar, kbar_l), steps, 1, torch)
     t_s1 = timed(lambda: B.dash_stage1_route(p, q, kbar, lists, ws), steps, 1, torch)
     t_s2 = timed(lambda: B.dash_stage2_attend(p, q, k, v, o, lists, ws), steps, 1, torch)
     od = torch.empty_like(q)
     t_dense = timed(lambda: B.dense_attn(p, q, k, v, od, ws), steps, warmup, torch)
-    res = dict(ms_step=t_all, ms_stage0=t_s0, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
-    del q, k, v, o, od, ws, lists, kbar
+    res = dict(ms_step=t_all, ms_stage0=t_s0, ms_stage0_learned=t_s0l, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
+    del q, k, v, o, od, ws, lists, kbar, kbar_l
     torch.cuda.empty_cache()
     return res
 
@@ -156,7 +160,7 @@ def bench_decode(w, steps, warmup, torch, B, make_inputs):
                bytes_stage1=bytes_s1, kv_gbs=bytes_kv / (t * 1e-3) / 1e9,
                total_gbs=(bytes_kv + bytes_s1) / (t * 1e-3) / 1e9,
                dense_gbs=dense_bytes / (t_dense * 1e-3) / 1e9)
-    del q, k, v, o, od, ws, lists, kbar
+    del q, k, v, o, od, ws, lists, kbar, kbar_l
     torch.cuda.empty_cache()
     return res
 
@@ -340,6 +344,11 @@ def main():
         "extras": {
             "chunk_sparsity": main_res["sparsity"],
             "ms": {k_: main_res[k_] for k_ in ("ms_step", "ms_stage0", "ms_stage1", "ms_stage2", "ms_dense")},
+            "stage0_learned": {"ms": main_res["ms_stage0_learned"],
+                               "k_read_GBps": w.batch * w.h_kv * w.n_kv * w.head_dim * 2 /
+                                              (main_res["ms_stage0_learned"] * 1e-3) / 1e9,
+                               "block_mean_k_read_GBps": w.batch * w.h_kv * w.n_kv * w.head_dim * 2 /
+                                                         (main_res["ms_stage0"] * 1e-3) / 1e9},
             "speedup_vs_dense": main_res["ms_dense"] / main_res["ms_step"],
             "stage2_speedup_vs_dense": main_res["ms_dense"] / main_res["ms_stage2"],
             "dense_tflops": tf(main_res["f_dense"], main_res["ms_dense"]),

@@ -95,6 +95,27 @@ int dash_attn_workspace_bytes(const dash_params* p, size_t* out_bytes);
 int dash_kbar_compress(const dash_params* p, const void* k, float* kbar,
                        int32_t first_chunk, int32_t n_chunks, void* stream);
 
+/* Stage 0 with a learned summary query (Sec. 3.1 Eq. 3; Alg. 1): the summary of a
+ * chunk is one softmax attention of the query over the chunk's own keys, with
+ * the keys as values: kbar_c = softmax(K_c qbar scale)^T K_c (scale as in
+ * dash_params, default 1/sqrt(d)).  A zero query gives dash_kbar_compress' result.
+ *   k           in  as for dash_kbar_compress
+ *   qbar        in  fp32 device pointer, 16-byte aligned, d contiguous; element
+ *               (b, r, c) starts at b*qbar_stride[0] + r*qbar_stride[1] +
+ *               c*qbar_stride[2] (elements; multiples of 4 for fp32 keys and of 8
+ *               for bf16 keys; 0 broadcasts): one vector per kv-head (Sec. 3.1:
+ *               strides {0, d, 0}) or one per chunk with the rotary embedding
+ *               already applied (Alg. 1: strides {h_kv*T_c*d or 0, T_c*d, d})
+ *   qbar_stride in  host pointer to 3 strides
+ *   kbar        out as for dash_kbar_compress (fp32; scores, softmax and the
+ *               weighted sum are evaluated in fp64 and rounded once)
+ *   first_chunk, n_chunks: as for dash_kbar_compress.
+ * Errors: DASH_EINVAL for null pointers, negative or misaligned strides or a chunk
+ * range outside [0, T_c). */
+int dash_kbar_summarize(const dash_params* p, const void* k, const float* qbar,
+                        const int64_t* qbar_stride, float* kbar, int32_t first_chunk,
+                        int32_t n_chunks, void* stream);
+
 /* Stage 1 (Eq. 4, GQA averaging, Prop. 1 bias; Alg. 2).
  *   q     in  [batch,h_q,n_q,d]
  *   kbar  in  fp32 summaries from dash_kbar_compress

@@ -45,6 +45,8 @@ _SIGNATURES = {
     "dash_mask_words": (ctypes.c_int32, [_P]),
     "dash_attn_workspace_bytes": (ctypes.c_int, [_P, ctypes.POINTER(ctypes.c_size_t)]),
     "dash_kbar_compress": (ctypes.c_int, [_P, _V, _V, ctypes.c_int32, ctypes.c_int32, _V]),
+    "dash_kbar_summarize": (ctypes.c_int, [_P, _V, _V, ctypes.POINTER(ctypes.c_int64), _V, ctypes.c_int32,
+                                           ctypes.c_int32, _V]),
     "dash_stage1_route": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_stage2_attend": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_attn_prefill": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
@@ -157,6 +159,22 @@ def dash_kbar_compress(p: dash_params, k: torch.Tensor, kbar: torch.Tensor,
                        first_chunk: int = 0, n_chunks: int = -1) -> None:
     _check(load_library().dash_kbar_compress(ctypes.byref(p), _ptr(k), _ptr(kbar), first_chunk, n_chunks,
                                              _stream()), "dash_kbar_compress")
+
+
+def dash_kbar_summarize(p: dash_params, k: torch.Tensor, qbar: torch.Tensor, kbar: torch.Tensor,
+                        first_chunk: int = 0, n_chunks: int = -1) -> None:
+    """qbar: fp32 tensor [h_kv, d] (one summary query per kv-head), [h_kv, T_c, d]
+    or [batch, h_kv, T_c, d] (one per chunk); only the strides are passed on."""
+    assert qbar.dtype == torch.float32 and qbar.stride(-1) == 1
+    if qbar.dim() == 2:
+        st = (0, qbar.stride(0), 0)
+    elif qbar.dim() == 3:
+        st = (0, qbar.stride(0), qbar.stride(1))
+    else:
+        st = (qbar.stride(0), qbar.stride(1), qbar.stride(2))
+    arr = (ctypes.c_int64 * 3)(*st)
+    _check(load_library().dash_kbar_summarize(ctypes.byref(p), _ptr(k), _ptr(qbar), arr, _ptr(kbar),
+                                              first_chunk, n_chunks, _stream()), "dash_kbar_summarize")
 
 
 def dash_stage1_route(p, q, kbar, lists: Lists, ws: torch.Tensor) -> None:

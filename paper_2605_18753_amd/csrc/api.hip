@@ -147,6 +147,23 @@ int dash_kbar_compress(const dash_params* p, const void* k, float* kbar, int32_t
              ? DASH_OK : DASH_ELAUNCH;
 }
 
+int dash_kbar_summarize(const dash_params* p, const void* k, const float* qbar,
+                        const int64_t* qbar_stride, float* kbar, int32_t first_chunk,
+                        int32_t n_chunks, void* stream) {
+  Layout L;
+  int rc = make_layout(p, &L);
+  if (rc != DASH_OK) return rc;
+  if (!k || !qbar || !qbar_stride || (!kbar && L.t_c > 0)) return DASH_EINVAL;
+  const int vec = p->dtype == DASH_BF16 ? 8 : 4;
+  for (int i = 0; i < 3; i++)
+    if (qbar_stride[i] < 0 || qbar_stride[i] % vec != 0) return DASH_EINVAL;
+  if (((uintptr_t)qbar & 15) != 0) return DASH_EINVAL;
+  if (n_chunks < 0) { first_chunk = 0; n_chunks = L.t_c; }
+  if (first_chunk < 0 || first_chunk + n_chunks > L.t_c) return DASH_EINVAL;
+  return launch_kbar_summarize(*p, L, k, qbar, qbar_stride, kbar, first_chunk, n_chunks,
+                               (hipStream_t)stream) == hipSuccess ? DASH_OK : DASH_ELAUNCH;
+}
+
 int dash_stage1_route(const dash_params* p, const void* q, const float* kbar, uint32_t* mask,
                       int32_t* blk_cnt, int32_t* blk_idx, float* blk_bias, float* tau,
                       void* workspace, size_t workspace_bytes, void* stream) {

@@ -1,5 +1,7 @@
-// Stage 0: block-mean key summaries (Sec. 3.1, Eq. 3 with the summary query at
-// its zero initial value, i.e. uniform pooling; Alg. 1).
+// Stage 0: key summaries of every complete chunk (Sec. 3.1; Alg. 1): the block mean
+// (Eq. 3 with the summary query at its zero initial value, i.e. uniform pooling)
+// and the learned form (Eq. 3: one softmax attention of a summary query over the
+// chunk's own keys, the keys serving as values).
 //
 // One workgroup per (chunk, kv-head, batch).  The chunk (block x d elements) is
 // streamed once with 16-byte loads; sums are accumulated in fp64, which is exact
@@ -51,6 +53,81 @@ __global__ __launch_bounds__(256) void kbar_compress_kernel(
   }
 }
 
+
+// Learned summary (Eq. 3; Alg. 1): kbar_c = softmax(K_c qbar / sqrt(d))^T K_c.
+// Same decomposition as the mean kernel: thread (r0, cg) owns the 16-byte column
+// group cg of rows r0, r0 + rp, ...; it keeps those rows in registers, so the
+// chunk is read once.  Scores, softmax and the weighted sum are fp64, so the
+// fp32 result is the correctly rounded value except in the rare case that the
+// exact one lies within ~1e-15 of a rounding boundary.
+template <typename T>
+__global__ __launch_bounds__(256) void kbar_summarize_kernel(
+    const T* __restrict__ k, const float* __restrict__ qbar, float* __restrict__ kbar, int block,
+    int d, int t_c, int first_chunk, int64_t ks_b, int64_t ks_h, int64_t ks_t, int64_t qs_b,
+    int64_t qs_h, int64_t qs_c, double scale) {
+  constexpr int VEC = elem<T>::kVec;
+  constexpr int MAXR = 16;                // rows per thread: block / rp <= 128 / 8
+  __shared__ double sm[2048];
+  __shared__ double sc[128], ew[128];
+  const int c = first_chunk + blockIdx.x;
+  const int r = blockIdx.y, b = blockIdx.z, h_kv = gridDim.y;
+  const int cg_n = d / VEC;              // 16-byte column groups per row (a power of two <= 32)
+  const int rp = 256 / cg_n;             // rows covered per pass
+  const int cg = threadIdx.x % cg_n, r0 = threadIdx.x / cg_n;
+  const int nrow = block / rp;
+  const T* base = k + b * ks_b + r * ks_h + (int64_t)c * block * ks_t + cg * VEC;
+  const float* qp = qbar + b * qs_b + r * qs_h + (int64_t)c * qs_c + cg * VEC;
+  double qv[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; e++) qv[e] = (double)qp[e];
+  u32x4 raw[MAXR];
+  auto key = [&](const u32x4& w, int e) -> double {
+    if constexpr (VEC == 8) return (double)((e & 1) ? bf16_hi(w[e >> 1]) : bf16_lo(w[e >> 1]));
+    else return (double)__uint_as_float(w[e]);
+  };
+  // scores s_t = <qbar, k_t> * scale: per-thread partial over its column group, then
+  // a butterfly over the cg_n lanes that share the row
+#pragma unroll
+  for (int i = 0; i < MAXR; i++) {
+    if (i < nrow) {
+      raw[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)(r0 + i * rp) * ks_t);
+      double part = 0.0;
+#pragma unroll
+      for (int e = 0; e < VEC; e++) part += qv[e] * key(raw[i], e);
+      for (int m = 1; m < cg_n; m <<= 1) part += __shfl_xor(part, m);
+      if (cg == 0) sc[r0 + i * rp] = part * scale;
+    }
+  }
+  __syncthreads();
+  double mx = sc[0];
+  for (int t = 1; t < block; t++) mx = fmax(mx, sc[t]);
+  if (threadIdx.x < block) ew[threadIdx.x] = exp(sc[threadIdx.x] - mx);
+  __syncthreads();
+  double den = 0.0;
+  for (int t = 0; t < block; t++) den += ew[t];
+  double acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; e++) acc[e] = 0.0;
+#pragma unroll
+  for (int i = 0; i < MAXR; i++) {
+    if (i < nrow) {
+      const double w = ew[r0 + i * rp];
+#pragma unroll
+      for (int e = 0; e < VEC; e++) acc[e] += w * key(raw[i], e);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; e++) sm[r0 * d + cg * VEC + e] = acc[e];
+  __syncthreads();
+  const int col = threadIdx.x;
+  if (col < d) {
+    double s = 0.0;
+    for (int rr = 0; rr < rp; rr++) s += sm[rr * d + col];
+    const int64_t o = (((int64_t)b * h_kv + r) * t_c + c) * d + col;
+    kbar[o] = (float)(s / den);
+  }
+}
+
 hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const void* k, float* kbar,
                                 int first_chunk, int n_chunks, hipStream_t st) {
   if (n_chunks <= 0) return hipSuccess;
@@ -63,6 +140,24 @@ hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const voi
     hipLaunchKernelGGL(kbar_compress_kernel<float>, grid, blk, 0, st, (const float*)k, kbar,
                        p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0], p.k_stride[1],
                        p.k_stride[2]);
+  return hipGetLastError();
+}
+
+hipError_t launch_kbar_summarize(const dash_params& p, const Layout& L, const void* k, const float* qbar,
+                                 const int64_t* qs, float* kbar, int first_chunk, int n_chunks,
+                                 hipStream_t st) {
+  if (n_chunks <= 0) return hipSuccess;
+  dim3 grid(n_chunks, p.h_kv, p.batch), blk(256);
+  // the logit scale in double: the default 1/sqrt(d) is not rounded through fp32
+  const double scale = p.scale > 0.f ? (double)p.scale : 1.0 / sqrt((double)p.head_dim);
+  if (p.dtype == DASH_BF16)
+    hipLaunchKernelGGL(kbar_summarize_kernel<uint16_t>, grid, blk, 0, st, (const uint16_t*)k, qbar, kbar,
+                       p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0], p.k_stride[1],
+                       p.k_stride[2], qs[0], qs[1], qs[2], scale);
+  else
+    hipLaunchKernelGGL(kbar_summarize_kernel<float>, grid, blk, 0, st, (const float*)k, qbar, kbar,
+                       p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0], p.k_stride[1],
+                       p.k_stride[2], qs[0], qs[1], qs[2], scale);
   return hipGetLastError();
 }
 

@@ -34,6 +34,9 @@ struct S1Out {
 
 hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const void* k, float* kbar,
                                 int first_chunk, int n_chunks, hipStream_t st);
+hipError_t launch_kbar_summarize(const dash_params& p, const Layout& L, const void* k, const float* qbar,
+                                 const int64_t* qs, float* kbar, int first_chunk, int n_chunks,
+                                 hipStream_t st);
 hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const void* q,
                                 const float* kbar, float* scores, hipStream_t st);
 // ksplit != NULL: bf16 MFMA scorer (the split of kbar is written to ksplit first);

@@ -38,6 +38,65 @@ def test_kbar_bit_exact(dtype, d, block, n):
     assert np.array_equal(got[:, :, 1], ref[:, :, 1]) and np.all(got[:, :, 0] == 7.0)
 
 
+@pytest.mark.parametrize("dtype,d,block,n,per_chunk", [
+    ("bf16", 128, 64, 1000, False), ("bf16", 64, 128, 1024, True), ("bf16", 128, 128, 640, True),
+    ("fp32", 64, 64, 640, False), ("fp32", 128, 128, 900, True)])
+def test_learned_summaries_match_oracle(dtype, d, block, n, per_chunk):
+    """Stage 0 with a learned summary query (Eq. 3; Alg. 1) against the fp64 oracle:
+    equal to 1 ulp of fp32, bit for bit on nearly every element."""
+    w = Workload("kbar_learned", 2, 4, 2, n, n, d, block, dtype=dtype)
+    q, k, v = gen(w)
+    p = B.make_params(q, k, v, None, block)
+    t_c = n // block
+    g = torch.Generator().manual_seed(5)
+    if per_chunk:
+        qbar = torch.randn((2, 2, t_c, d), generator=g) * 3.0     # [batch, h_kv, T_c, d]
+    else:
+        qbar = torch.randn((2, d), generator=g) * 3.0             # [h_kv, d]
+    qbar = qbar.float().to(DEV)
+    kbar = torch.zeros(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    B.dash_kbar_summarize(p, k, qbar, kbar)
+    torch.cuda.synchronize()
+    qn = qbar.cpu().numpy().astype(np.float64)
+    qn = qn if per_chunk else qn[None, :, None, :]
+    ref = orc.local_attention_summaries(U.to_np(k), qn, block).astype(np.float32)
+    got = kbar.cpu().numpy()
+    ud = U.ulp_diff(got, ref)
+    assert ud.max() <= 1 and (ud > 0).mean() <= 1e-4, (ud.max(), (ud > 0).mean())
+    # the weights are not uniform here: the result must differ from the block mean
+    assert np.abs(got - orc.block_mean_summaries(U.to_np(k), block)).max() > 1e-2
+    # a zero query is the block mean, bit for bit
+    kz = torch.zeros_like(kbar)
+    B.dash_kbar_summarize(p, k, torch.zeros((2, d), dtype=torch.float32, device=DEV), kz)
+    km = torch.zeros_like(kbar)
+    B.dash_kbar_compress(p, k, km)
+    torch.cuda.synchronize()
+    assert torch.equal(kz, km)
+    # partial update: only chunk 1 is rewritten
+    kbar2 = torch.full_like(kbar, 7.0)
+    B.dash_kbar_summarize(p, k, qbar, kbar2, 1, 1)
+    torch.cuda.synchronize()
+    got2 = kbar2.cpu().numpy()
+    assert np.array_equal(got2[:, :, 1], got[:, :, 1]) and np.all(got2[:, :, 0] == 7.0)
+
+
+@pytest.mark.parametrize("name,h_q,h_kv,n,d,block,causal", [
+    ("learned_gqa4", 8, 2, 1000, 128, 64, True), ("learned_gqa4_d64_noncausal", 8, 2, 2048, 64, 64, False)])
+def test_prefill_with_learned_summaries(name, h_q, h_kv, n, d, block, causal):
+    """Whole path on learned summaries: dash_kbar_summarize, then the Stage-1 and
+    Stage-2 entry points, every row against the oracle run on the oracle's summaries."""
+    w = Workload(name, 1, h_q, h_kv, n, n, d, block, causal=causal, offset_sigma=1.0)
+    q, k, v = gen(w)
+    t_c = n // block
+    qbar = (torch.randn((h_kv, t_c, d), generator=torch.Generator().manual_seed(9)) * 2.0).float().to(DEV)
+    run = U.run_prefill_learned(w, q, k, v, qbar)
+    qn = qbar.cpu().numpy().astype(np.float64)
+    rep, err = U.check_against_oracle(
+        w, q, k, v, run, summaries=lambda b, r, kn: orc.local_attention_summaries(kn, qn[r], block))
+    print(f"{name}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    assert 0.02 < rep.sparsity < 0.98
+
+
 def test_prefill_c1_fp32_full():
     w = C1
     q, k, v = gen(w)

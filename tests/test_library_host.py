@@ -33,7 +33,8 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     names = header_functions()
-    assert {"dash_attn_prefill", "dash_attn_decode", "dense_attn", "dash_kbar_compress"} <= names
+    assert {"dash_attn_prefill", "dash_attn_decode", "dense_attn", "dash_kbar_compress",
+            "dash_kbar_summarize"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert names == set(B.exported_symbols())
@@ -88,6 +89,22 @@ def test_null_and_workspace_errors():
     assert lib.dash_attn_workspace_bytes(None, None) == -1
     p.q_stride[2] = 100                                                                    # misaligned rows
     assert lib.dense_attn(ctypes.byref(p), 256, 256, 256, 256, 256, need, None) == -1
+
+
+def test_summarize_argument_errors():
+    lib = B.load_library()
+    p = params()
+    ok = (ctypes.c_int64 * 3)(0, 128, 0)
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, None, ok, 256, 0, -1, None) == -1     # no query
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, 256, None, 256, 0, -1, None) == -1    # no strides
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, 264, ok, 256, 0, -1, None) == -1      # query not 16-byte aligned
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, 256, (ctypes.c_int64 * 3)(0, 100, 0), 256, 0, -1,
+                                   None) == -1                                                # stride not a multiple of 8
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, 256, (ctypes.c_int64 * 3)(0, -128, 0), 256, 0, -1,
+                                   None) == -1
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, 256, ok, 256, 15, 2, None) == -1      # 16 chunks: 15..16
+    assert lib.dash_kbar_summarize(ctypes.byref(p), 256, 256, ok, 256, 3, 0, None) == 0        # empty range: nothing to do
+    assert lib.dash_kbar_compress(ctypes.byref(p), 256, 256, 15, 2, None) == -1
 
 
 def test_strerror():
