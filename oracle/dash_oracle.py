@@ -328,6 +328,7 @@ class DashParams:
     sigma: float = 1.0
     causal: bool = True
     scale: Optional[float] = None      # None -> 1/sqrt(d)
+    window: int = 0                    # complete chunks before the diagonal one that are always attended
 
 
 @dataclass
@@ -352,8 +353,13 @@ def dash_row_at(qh, k, v, kbar, prm: DashParams, pos: int, ident=(0, 0, 0)) -> R
     summaries kbar [T_c, d].
 
     Causal: candidates are the chunks strictly before the query's own chunk,
-    and the diagonal branch is the causal part of that chunk.  Non-causal: all
-    chunks are candidates and there is no diagonal branch.
+    and the diagonal branch is the causal part of that chunk (Alg. 2).  With
+    prm.window = W > 0 the W complete chunks just before the query's own are
+    part of the always-attended local set as well (the local window of the
+    trained models, App. B.1: the diagonal block and the last block, W = 1):
+    they leave the candidate set and their tokens join the diagonal branch
+    D_i of Proposition 1 with bias 0.  Non-causal: all chunks are candidates
+    and there is no diagonal branch.
     """
     qh = np.asarray(qh, dtype=np.float64)
     g_q, d = qh.shape
@@ -361,7 +367,7 @@ def dash_row_at(qh, k, v, kbar, prm: DashParams, pos: int, ident=(0, 0, 0)) -> R
     scale = prm.scale if prm.scale is not None else 1.0 / math.sqrt(d)
     blk = prm.block
     if prm.causal:
-        n_cand = pos // blk
+        n_cand = max(pos // blk - prm.window, 0)
         diag = (n_cand * blk, pos + 1)
     else:
         assert n_kv % blk == 0

@@ -264,3 +264,61 @@ def test_learned_summary_is_a_convex_combination_and_shift_equivariant():
     # the scale multiplies the logits: scale 0 is uniform pooling whatever the query
     got0 = orc.local_attention_summaries(k, qbar, 32, scale=0.0)
     assert np.allclose(got0, body.mean(axis=2), atol=1e-6)
+
+
+# --------------------------------------------------------------------------
+# local window of always-attended chunks (App. B.1: the diagonal block and the last block)
+# --------------------------------------------------------------------------
+def _window_case(seed=21, n=160, d=8, blk=16, g=2):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((g, d))
+    k = rng.standard_normal((n, d)) + np.repeat(rng.standard_normal((n // blk, d)), blk, axis=0)
+    v = rng.standard_normal((n, d))
+    return q, k, v, orc.block_mean_summaries(k, blk)
+
+
+def test_window_moves_chunks_from_the_candidates_to_the_local_branch():
+    q, k, v, kb = _window_case()
+    pos = 150                                              # chunk 9 of 10
+    r0 = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16), pos)
+    r1 = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16, window=1), pos)
+    r2 = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16, window=2), pos)
+    assert (r0.n_cand, r1.n_cand, r2.n_cand) == (9, 8, 7)
+    assert r1.diag == (8 * 16, pos + 1) and r2.diag == (7 * 16, pos + 1)
+    assert all(c < 8 for c in r1.routed) and all(c < 7 for c in r2.routed)
+    # the window is capped by the start of the sequence: a query in chunk 1 with W = 2 sees tokens 0..pos
+    r = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16, window=2), 20)
+    assert r.n_cand == 0 and r.diag == (0, 21) and r.routed.size == 0
+
+
+def test_window_rows_without_candidates_are_causal_softmax_over_the_window():
+    # with nothing left to route, the row is plain causal attention over the local tokens
+    q, k, v, kb = _window_case(seed=22)
+    pos = 40                                               # chunk 2; W = 2 covers chunks 0 and 1
+    r = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16, window=2), pos)
+    ref = orc.dense_attention(q, k[:pos + 1], v[:pos + 1], 1 / np.sqrt(8.0), False)   # rows = the heads
+    assert np.allclose(r.o, ref, atol=1e-12)
+
+
+def test_window_equals_forcing_the_chunks_by_hand():
+    # the windowed row is the bias form over (routed set of the shorter candidate list) + (window and
+    # diagonal tokens at bias 0): build that from the parts and compare
+    q, k, v, kb = _window_case(seed=23)
+    pos = 150
+    prm = orc.DashParams(block=16, window=1, sigma=2.0)
+    r = orc.dash_row_at(q, k, v, kb, prm, pos)
+    x, tau, _, w = orc.route_token(q, kb[:8], prm.alpha, prm.gamma, 1 / np.sqrt(8.0))
+    routed, bias = orc.prior_bias(w, prm.sigma)
+    o = orc.attend_bias_form(q, k, v, 1 / np.sqrt(8.0), 16, routed, bias, 8 * 16, pos + 1)
+    assert np.array_equal(r.routed, routed) and np.allclose(r.o, o, atol=1e-13)
+    # and it differs from the windowless row unless chunk 8 happened to be routed with bias 0
+    r0 = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16, sigma=2.0), pos)
+    assert np.abs(r0.o - r.o).max() > 1e-6
+
+
+def test_window_gamma_to_zero_is_dense_causal_attention():
+    q, k, v, kb = _window_case(seed=24)
+    pos = 150
+    r = orc.dash_row_at(q, k, v, kb, orc.DashParams(block=16, window=1, gamma=1e-9), pos)
+    ref = orc.dense_attention(q, k[:pos + 1], v[:pos + 1], 1 / np.sqrt(8.0), False)
+    assert np.allclose(r.o, ref, atol=1e-7)
