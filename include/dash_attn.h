@@ -67,6 +67,10 @@ typedef struct dash_params {
   float gamma;         /* Stage-1 temperature (Eq. 4), > 0                            */
   float sigma;         /* prior strength (Sec. 3.4), > 0; large => pure block mask    */
   float scale;         /* logit scale; <= 0 selects 1/sqrt(head_dim)                  */
+  int32_t window;      /* causal only: complete chunks just before the query's own
+                          that are always attended with bias 0 and leave the
+                          candidate set (0: Alg. 2; 1: the diagonal block and the
+                          last block, the local window of App. B.1); 0..8            */
   int64_t q_stride[3]; /* batch, head, token strides of q, in elements               */
   int64_t k_stride[3];
   int64_t v_stride[3];
@@ -123,11 +127,12 @@ int dash_kbar_summarize(const dash_params* p, const void* k, const float* qbar,
  * be NULL (not produced); mask and blk_bias may be NULL, in which case they are
  * kept inside the workspace for dash_stage2_attend:
  *   mask     uint32 [.., dash_mask_words]   bit c set iff chunk c is attended
- *            (routed chunks, plus the diagonal chunk when causal)
+ *            (routed chunks, plus, when causal, the window chunks and the
+ *            diagonal chunk)
  *   blk_cnt  int32  [..]                    number of attended chunks
  *   blk_idx  int32  [.., dash_list_stride]  their ids, ascending (diagonal last)
  *   blk_bias fp32   [.., dash_list_stride]  d_{i,c} in the same order (0 for the
- *            diagonal chunk); entries past blk_cnt are unspecified
+ *            window and diagonal chunks); entries past blk_cnt are unspecified
  *   tau      fp32   [batch,h_q,n_q]         entmax threshold of every query head
  *            in the domain x = gamma (alpha-1) <q,kbar> scale (0 if no candidate) */
 int dash_stage1_route(const dash_params* p, const void* q, const float* kbar,

@@ -31,7 +31,7 @@ class dash_params(ctypes.Structure):
         ("n_q", ctypes.c_int32), ("n_kv", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("block_size", ctypes.c_int32), ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("alpha", ctypes.c_float), ("gamma", ctypes.c_float), ("sigma", ctypes.c_float),
-        ("scale", ctypes.c_float),
+        ("scale", ctypes.c_float), ("window", ctypes.c_int32),
         ("q_stride", ctypes.c_int64 * 3), ("k_stride", ctypes.c_int64 * 3),
         ("v_stride", ctypes.c_int64 * 3), ("o_stride", ctypes.c_int64 * 3),
     ]
@@ -94,7 +94,7 @@ def _stream():
 
 def make_params(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: Optional[torch.Tensor],
                 block: int, alpha: float = 1.5, gamma: float = 1.0, sigma: float = 1.0,
-                causal: bool = True, scale: float = 0.0) -> dash_params:
+                causal: bool = True, scale: float = 0.0, window: int = 0) -> dash_params:
     """q [B,H_q,n_q,d]; k, v [B,H_kv,n_kv,d]; last dim contiguous."""
     p = dash_params()
     p.batch, p.h_q, p.n_q, p.head_dim = q.shape
@@ -103,6 +103,7 @@ def make_params(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: Optional[t
     p.causal = int(causal)
     p.dtype = DASH_BF16 if q.dtype == torch.bfloat16 else DASH_F32
     p.alpha, p.gamma, p.sigma, p.scale = alpha, gamma, sigma, scale
+    p.window = window
     for name, t in (("q_stride", q), ("k_stride", k), ("v_stride", v), ("o_stride", o if o is not None else q)):
         assert t.stride(3) == 1, "head_dim must be contiguous"
         getattr(p, name)[:] = [t.stride(0), t.stride(1), t.stride(2)]

@@ -21,6 +21,7 @@ int make_layout(const dash_params* p, Layout* L, bool routing) {
   if (!(p->alpha > 1.f) || !(p->gamma > 0.f) || !(p->sigma > 0.f)) return DASH_EINVAL;
   if (!isfinite(p->alpha) || !isfinite(p->gamma) || !isfinite(p->scale)) return DASH_EINVAL;
   if (p->causal != 0 && p->causal != 1) return DASH_EINVAL;
+  if (p->window < 0 || p->window > 8 || (p->window > 0 && !p->causal)) return DASH_EINVAL;
   if (p->dtype != DASH_F32 && p->dtype != DASH_BF16) return DASH_EINVAL;
   if (p->head_dim < 1 || p->block_size < 1) return DASH_EINVAL;
   if (routing && !p->causal && p->n_kv % p->block_size != 0) return DASH_EINVAL;

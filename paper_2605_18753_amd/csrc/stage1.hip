@@ -16,7 +16,9 @@
 //   3. averages the per-head probabilities over the GQA group, takes
 //      mu = mean ln w over the support, d = (ln w - mu)/sigma, and emits the
 //      bit-packed mask plus the compacted (index, bias) list via wave ballots,
-//      appending the diagonal chunk with bias 0 when causal.
+//      appending, when causal, the always-attended local chunks with bias 0: the
+//      `window` complete chunks before the query's own (they are not candidates)
+//      and the query's own (diagonal) chunk.
 // Nothing of the score matrix ever goes to HBM on the MFMA path.
 #include <math.h>
 
@@ -34,7 +36,7 @@ struct S1Args {
   int32_t* idx;
   float* bias;
   float* tau;
-  int batch, h_q, h_kv, g_q, n_q, block, t_c, t_all, words, pos0, causal, ld;
+  int batch, h_q, h_kv, g_q, n_q, block, t_c, t_all, words, pos0, causal, window, ld;
   int64_t qs_b, qs_h, qs_t;
   float xscale, pexp, alpha, inv_sigma;
 };
@@ -321,13 +323,20 @@ __device__ __forceinline__ void emit_token(const float* S, const S1Args& a, uint
     running += __popcll(bal);
   }
   __builtin_amdgcn_wave_barrier();
-  if (a.causal && lane == 0) {
-    const int cd = (a.pos0 + tok) / a.block;   // the query's own chunk
-    if (oidx) oidx[running] = cd;
-    obias[running] = 0.f;
-    mw[cd >> 5] |= 1u << (cd & 31);
+  if (a.causal) {
+    // the always-attended local set, bias 0: the chunks of the window, then the
+    // query's own chunk
+    const int cd = (a.pos0 + tok) / a.block;
+    const int c0 = max(cd - a.window, 0);
+    if (lane == 0) {
+      for (int c = c0; c <= cd; c++) {
+        if (oidx) oidx[running + c - c0] = c;
+        obias[running + c - c0] = 0.f;
+        mw[c >> 5] |= 1u << (c & 31);
+      }
+    }
+    running += cd - c0 + 1;
   }
-  if (a.causal) running += 1;
   __builtin_amdgcn_wave_barrier();
   if (a.cnt && lane == 0) a.cnt[base] = running;
   uint32_t* om = a.mask + base * a.words;
@@ -349,7 +358,7 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
   const int r = hbi % a.h_kv, b = hbi / a.h_kv;
   const int tok0 = tile * tokt;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  int n_cand = a.causal ? (a.pos0 + tok0) / a.block : a.t_c;
+  int n_cand = a.causal ? max((a.pos0 + tok0) / a.block - a.window, 0) : a.t_c;
   if (n_cand > a.t_c) n_cand = a.t_c;
 
   if (n_cand > 0) {
@@ -622,7 +631,7 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
   a.q = q; a.ksplit = ksplit; a.scores = scores;
   a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
   a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.block = p.block_size;
-  a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal;
+  a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal; a.window = p.window;
   a.ld = ((L.t_c + 15) / 16) * 16 + 4;
   a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
   a.xscale = L.xscale; a.pexp = L.pexp; a.alpha = p.alpha; a.inv_sigma = 1.f / p.sigma;

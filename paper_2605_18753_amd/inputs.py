@@ -41,6 +41,7 @@ class Workload:
     gamma: float = 1.0
     sigma: float = 1.0
     causal: bool = True
+    window: int = 0              # always-attended complete chunks before the diagonal one
     dtype: str = "bf16"          # "bf16" | "fp32"
     offset_sigma: float = 0.5    # std of the per-block key offset
     needles: int = 0             # >0: needle recipe instead of offsets

@@ -37,7 +37,7 @@ class GpuRun:
 def run_prefill(w: Workload, q, k, v, *, want_idx=True) -> GpuRun:
     dev = q.device
     o = torch.empty_like(q)
-    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal)
+    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal, window=w.window)
     kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
     lists = B.Lists.allocate(p, dev, idx=want_idx)
     ws = B.alloc_workspace(p, dev)
@@ -51,7 +51,7 @@ def run_prefill_learned(w: Workload, q, k, v, qbar: torch.Tensor) -> GpuRun:
     the Stage-1 and Stage-2 entry points."""
     dev = q.device
     o = torch.empty_like(q)
-    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal)
+    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal, window=w.window)
     kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
     lists = B.Lists.allocate(p, dev)
     ws = B.alloc_workspace(p, dev)
@@ -73,7 +73,7 @@ def ulp_diff(a: np.ndarray, b: np.ndarray) -> np.ndarray:
 def run_decode(w: Workload, q, k, v, kbar: Optional[torch.Tensor] = None) -> GpuRun:
     dev = q.device
     o = torch.empty_like(q)
-    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, True)
+    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, True, window=w.window)
     if kbar is None:
         kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
         B.dash_kbar_compress(p, k, kbar)
@@ -85,7 +85,8 @@ def run_decode(w: Workload, q, k, v, kbar: Optional[torch.Tensor] = None) -> Gpu
 
 
 def oracle_params(w: Workload) -> orc.DashParams:
-    return orc.DashParams(block=w.block, alpha=w.alpha, gamma=w.gamma, sigma=w.sigma, causal=w.causal)
+    return orc.DashParams(block=w.block, alpha=w.alpha, gamma=w.gamma, sigma=w.sigma, causal=w.causal,
+                          window=w.window)
 
 
 @dataclass
@@ -130,10 +131,14 @@ def compare_row(rr: orc.RowResult, w: Workload, mask_words: np.ndarray, cnt: int
     gpu_set = set(np.nonzero(bits)[0].tolist())
     ref_set = set(rr.routed.tolist())
     diag_chunk = None
+    local: List[int] = []            # always-attended chunks: the window, then the diagonal chunk
     if w.causal:
         diag_chunk = rr.pos // w.block
-        assert diag_chunk in gpu_set, f"row {rr.b,rr.r,rr.iq}: diagonal chunk missing"
-        gpu_set.discard(diag_chunk)
+        local = list(range(rr.n_cand, diag_chunk + 1))
+        assert len(local) == min(w.window, diag_chunk) + 1
+        for c in local:
+            assert c in gpu_set, f"row {rr.b,rr.r,rr.iq}: local chunk {c} missing"
+            gpu_set.discard(c)
     assert all(c < rr.n_cand for c in gpu_set), f"row {rr.b,rr.r,rr.iq}: non-candidate chunk attended"
     rep.blocks += rr.n_cand
     rep.kept += len(ref_set)
@@ -150,14 +155,14 @@ def compare_row(rr: orc.RowResult, w: Workload, mask_words: np.ndarray, cnt: int
         else:
             rep.mismatched += 1
     # list structure: count, ascending ids, diagonal last, agreement with the mask
-    n_expected = len(gpu_set) + (1 if w.causal else 0)
+    n_expected = len(gpu_set) + len(local)
     assert cnt == n_expected, f"row {rr.b,rr.r,rr.iq}: cnt {cnt} != popcount {n_expected}"
     if idx is not None:
         ids = idx[:cnt].tolist()
-        want = sorted(gpu_set) + ([diag_chunk] if w.causal else [])
+        want = sorted(gpu_set) + local
         assert ids == want, f"row {rr.b,rr.r,rr.iq}: idx list {ids[:8]}.. != mask order"
-    if w.causal:
-        assert bias[cnt - 1] == 0.0
+    for j in range(len(local)):
+        assert bias[cnt - 1 - j] == 0.0
     # bias of the chunks both sides keep (skip rows whose support differs: mu shifts)
     if not diff and len(ref_set):
         order = sorted(gpu_set)

@@ -121,6 +121,10 @@ SMALL = [
     ("single_chunk", 1, 4, 1, 50, 128, 64, {}),
     ("exactly_one_block", 1, 4, 1, 64, 64, 64, {}),
     ("noncausal_bf16", 1, 4, 2, 768, 128, 64, {"causal": False}),
+    # local window: the last complete chunk(s) always attended, not routed (App. B.1)
+    ("window1_gqa4", 1, 8, 2, 1000, 128, 64, {"window": 1}),
+    ("window2_gqa8_b128_d64", 1, 8, 1, 1536, 64, 128, {"window": 2, "offset_sigma": 1.0}),
+    ("window1_one_chunk_only", 1, 4, 1, 100, 128, 64, {"window": 1}),
 ]
 
 
@@ -137,7 +141,8 @@ def test_prefill_bf16_small(case):
 
 @pytest.mark.parametrize("case", [("fp32_gqa2", 1, 4, 2, 500, 64, 64, {}),
                                   ("fp32_gqa4_d128_b128", 2, 4, 1, 700, 128, 128, {"alpha": 2.0}),
-                                  ("fp32_noncausal_sigma", 1, 2, 1, 512, 128, 64, {"causal": False, "sigma": 4.0})],
+                                  ("fp32_noncausal_sigma", 1, 2, 1, 512, 128, 64, {"causal": False, "sigma": 4.0}),
+                                  ("fp32_window1", 1, 4, 2, 600, 64, 64, {"window": 1})],
                          ids=lambda c: c[0])
 def test_prefill_fp32_small(case):
     name, batch, h_q, h_kv, n, d, block, extra = case
@@ -169,7 +174,8 @@ def test_dense_attn(dtype, causal, n, d, hq, hkv):
     assert worst <= (2e-2 if dtype == "bf16" else 1e-5), worst
 
 
-@pytest.mark.parametrize("n_kv,extra", [(3000, {}), (4096, {}), (700, {"alpha": 2.0}), (63, {}), (2049, {"sigma": 1e8})])
+@pytest.mark.parametrize("n_kv,extra", [(3000, {}), (4096, {}), (700, {"alpha": 2.0}), (63, {}), (2049, {"sigma": 1e8}),
+                                         (3000, {"window": 1}), (4096, {"window": 2}), (100, {"window": 3})])
 def test_decode_small(n_kv, extra):
     w = Workload("decode", 3, 8, 2, 1, n_kv, 128, 64, offset_sigma=0.7, seed=9, **extra)
     q, k, v = gen(w)

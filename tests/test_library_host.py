@@ -57,6 +57,7 @@ def test_workspace_and_list_sizes():
     (dict(h_q=7), -1), (dict(alpha=1.0), -1), (dict(alpha=0.5), -1), (dict(sigma=0.0), -1),
     (dict(gamma=-1.0), -1), (dict(batch=0), -1), (dict(n_q=2048), -1), (dict(causal=2), -1),
     (dict(dtype=3), -1), (dict(causal=0, n_q=1000, n_kv=1000), -1),
+    (dict(window=-1), -1), (dict(window=9), -1), (dict(window=1, causal=0), -1),
     (dict(head_dim=96), -2), (dict(block_size=32), -2), (dict(h_q=64, h_kv=2), -2),
     (dict(n_q=100, n_kv=1001), -2), (dict(n_q=262144, n_kv=262144), -2),
 ])
