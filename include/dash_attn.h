@@ -169,6 +169,27 @@ int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache,
                      float* blk_bias, float* tau,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* One decode step for a batch of sequences of different lengths sharing one cache
+ * allocation (Sec. 3.5, the decoding regime of a serving loop): as
+ * dash_attn_decode, except that sequence b holds seq_lens[b] tokens (its current
+ * token included) in rows 0 .. seq_lens[b]-1 of its k_cache / v_cache slice and
+ * its query sits at position seq_lens[b]-1; p->n_kv is the capacity (row count)
+ * of the cache and sizes the strides, lists and workspace.
+ *   seq_lens      in  int32 device pointer [batch]; values outside [1, n_kv] are
+ *                 clamped into that range by the kernels (never read out of bounds)
+ *   update_cache  != 0: the block-mean summary of a chunk that a sequence's current
+ *                 token completes (seq_lens[b] % block_size == 0) is written into
+ *                 kbar_cache first, per sequence; 0: kbar_cache is read only (the
+ *                 caller maintains it, e.g. with dash_kbar_summarize)
+ * kbar_cache [batch,h_kv,floor(n_kv/block),d]; only the summaries of a sequence's
+ * complete chunks before its current one are read.  bf16 only (DASH_EUNSUPPORTED
+ * otherwise); DASH_EINVAL for a NULL seq_lens. */
+int dash_attn_decode_ragged(const dash_params* p, const void* q, const void* k_cache,
+                            const void* v_cache, float* kbar_cache, const int32_t* seq_lens,
+                            int32_t update_cache, void* o, uint32_t* mask, int32_t* blk_cnt,
+                            int32_t* blk_idx, float* blk_bias, float* tau, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
 /* Dense reference attention (Eq. 1), same tensors and layouts, no routing.
  * The denominator of every speed-up figure.  alpha/gamma/sigma/block_size are
  * ignored except for validation. */

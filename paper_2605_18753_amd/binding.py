@@ -51,6 +51,8 @@ _SIGNATURES = {
     "dash_stage2_attend": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_attn_prefill": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_attn_decode": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
+    "dash_attn_decode_ragged": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_int32, _V, _V, _V, _V, _V, _V, _V,
+                                               ctypes.c_size_t, _V]),
     "dense_attn": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
@@ -206,6 +208,17 @@ def dash_attn_decode(p, q, k_cache, v_cache, kbar_cache, o, lists: Lists, ws: to
                                            _ptr(kbar_cache), _ptr(o), _ptr(lists.mask), _ptr(lists.cnt),
                                            _ptr(lists.idx), _ptr(lists.bias), _ptr(lists.tau), wp, wn,
                                            _stream()), "dash_attn_decode")
+
+
+def dash_attn_decode_ragged(p, q, k_cache, v_cache, kbar_cache, seq_lens: torch.Tensor, o, lists: Lists,
+                            ws: torch.Tensor, update_cache: bool = True) -> None:
+    assert seq_lens.dtype == torch.int32 and seq_lens.is_contiguous() and seq_lens.numel() == p.batch
+    wp, wn = _ws_ptr(ws)
+    _check(load_library().dash_attn_decode_ragged(ctypes.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                                  _ptr(kbar_cache), _ptr(seq_lens), int(update_cache), _ptr(o),
+                                                  _ptr(lists.mask), _ptr(lists.cnt), _ptr(lists.idx),
+                                                  _ptr(lists.bias), _ptr(lists.tau), wp, wn, _stream()),
+           "dash_attn_decode_ragged")
 
 
 def dense_attn(p, q, k, v, o, ws: torch.Tensor) -> None:

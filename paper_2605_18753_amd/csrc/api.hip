@@ -204,26 +204,48 @@ int dash_attn_prefill(const dash_params* p, const void* q, const void* k, const 
   return run_stage2(p, L, q, k, v, o, mask, blk_bias, (char*)workspace, false, st);
 }
 
-int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache, const void* v_cache,
-                     float* kbar_cache, void* o, uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx,
-                     float* blk_bias, float* tau, void* workspace, size_t workspace_bytes,
-                     void* stream) {
+static int decode_impl(const dash_params* p, const void* q, const void* k_cache, const void* v_cache,
+                       float* kbar_cache, const int32_t* seq_lens, bool update_cache, void* o,
+                       uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx, float* blk_bias, float* tau,
+                       void* workspace, size_t workspace_bytes, void* stream) {
   Layout L;
   int rc = make_layout(p, &L);
   if (rc != DASH_OK) return rc;
   if (p->n_q != 1 || !p->causal) return DASH_EINVAL;
   if (!q || !k_cache || !v_cache || (!kbar_cache && L.t_c > 0) || !o) return DASH_EINVAL;
+  if (seq_lens && p->dtype != DASH_BF16) return DASH_EUNSUPPORTED;
   if ((rc = check_ws(L, workspace, workspace_bytes)) != DASH_OK) return rc;
+  L.seq_lens = seq_lens;
   hipStream_t st = (hipStream_t)stream;
-  if (p->n_kv % p->block_size == 0) {
-    // the current token completes chunk t_c - 1: summarise it now; it becomes a
+  if (update_cache) {
+    // a current token that completes a chunk: summarise that chunk now; it becomes a
     // candidate only for later positions
-    if (launch_kbar_compress(*p, L, k_cache, kbar_cache, L.t_c - 1, 1, st) != hipSuccess)
-      return DASH_ELAUNCH;
+    hipError_t e = hipSuccess;
+    if (seq_lens) e = launch_kbar_compress_completed(*p, L, k_cache, kbar_cache, st);
+    else if (p->n_kv % p->block_size == 0) e = launch_kbar_compress(*p, L, k_cache, kbar_cache, L.t_c - 1, 1, st);
+    if (e != hipSuccess) return DASH_ELAUNCH;
   }
   rc = run_stage1(p, L, q, kbar_cache, mask, blk_cnt, blk_idx, blk_bias, tau, (char*)workspace, st);
   if (rc != DASH_OK) return rc;
   return run_stage2(p, L, q, k_cache, v_cache, o, mask, blk_bias, (char*)workspace, false, st);
+}
+
+int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache, const void* v_cache,
+                     float* kbar_cache, void* o, uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx,
+                     float* blk_bias, float* tau, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  return decode_impl(p, q, k_cache, v_cache, kbar_cache, nullptr, true, o, mask, blk_cnt, blk_idx,
+                     blk_bias, tau, workspace, workspace_bytes, stream);
+}
+
+int dash_attn_decode_ragged(const dash_params* p, const void* q, const void* k_cache,
+                            const void* v_cache, float* kbar_cache, const int32_t* seq_lens,
+                            int32_t update_cache, void* o, uint32_t* mask, int32_t* blk_cnt,
+                            int32_t* blk_idx, float* blk_bias, float* tau, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  if (!seq_lens) return DASH_EINVAL;
+  return decode_impl(p, q, k_cache, v_cache, kbar_cache, seq_lens, update_cache != 0, o, mask, blk_cnt,
+                     blk_idx, blk_bias, tau, workspace, workspace_bytes, stream);
 }
 
 int dense_attn(const dash_params* p, const void* q, const void* k, const void* v, void* o,

@@ -15,11 +15,19 @@ namespace dash {
 template <typename T>
 __global__ __launch_bounds__(256) void kbar_compress_kernel(
     const T* __restrict__ k, float* __restrict__ kbar, int block,
-    int d, int t_c, int first_chunk, int64_t ks_b, int64_t ks_h, int64_t ks_t) {
+    int d, int t_c, int first_chunk, int64_t ks_b, int64_t ks_h, int64_t ks_t,
+    const int32_t* __restrict__ seq_lens, int n_kv) {
   constexpr int VEC = elem<T>::kVec;
   __shared__ double sm[2048];
-  const int c = first_chunk + blockIdx.x;
+  int c = first_chunk + blockIdx.x;
   const int r = blockIdx.y, b = blockIdx.z, h_kv = gridDim.y;
+  if (seq_lens) {
+    // decode with per-sequence lengths: only the chunk that the sequence's current
+    // token completes, if it completes one
+    const int len = min(max(seq_lens[b], 1), n_kv);
+    if (len % block != 0) return;
+    c = len / block - 1;
+  }
   const int cg_n = d / VEC;              // 16-byte column groups per row
   const int rp = 256 / cg_n;             // rows covered per pass
   const int cg = threadIdx.x % cg_n, r0 = threadIdx.x / cg_n;
@@ -135,11 +143,28 @@ hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const voi
   if (p.dtype == DASH_BF16)
     hipLaunchKernelGGL(kbar_compress_kernel<uint16_t>, grid, blk, 0, st, (const uint16_t*)k, kbar,
                        p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0],
-                       p.k_stride[1], p.k_stride[2]);
+                       p.k_stride[1], p.k_stride[2], (const int32_t*)nullptr, p.n_kv);
   else
     hipLaunchKernelGGL(kbar_compress_kernel<float>, grid, blk, 0, st, (const float*)k, kbar,
                        p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0], p.k_stride[1],
-                       p.k_stride[2]);
+                       p.k_stride[2], (const int32_t*)nullptr, p.n_kv);
+  return hipGetLastError();
+}
+
+// Decode with per-sequence lengths (L.seq_lens): one workgroup per (kv-head, batch)
+// summarises the chunk that sequence's current token completes, if any.
+hipError_t launch_kbar_compress_completed(const dash_params& p, const Layout& L, const void* k, float* kbar,
+                                          hipStream_t st) {
+  if (L.t_c == 0) return hipSuccess;
+  dim3 grid(1, p.h_kv, p.batch), blk(256);
+  if (p.dtype == DASH_BF16)
+    hipLaunchKernelGGL(kbar_compress_kernel<uint16_t>, grid, blk, 0, st, (const uint16_t*)k, kbar,
+                       p.block_size, p.head_dim, L.t_c, 0, p.k_stride[0], p.k_stride[1], p.k_stride[2],
+                       L.seq_lens, p.n_kv);
+  else
+    hipLaunchKernelGGL(kbar_compress_kernel<float>, grid, blk, 0, st, (const float*)k, kbar,
+                       p.block_size, p.head_dim, L.t_c, 0, p.k_stride[0], p.k_stride[1], p.k_stride[2],
+                       L.seq_lens, p.n_kv);
   return hipGetLastError();
 }
 

@@ -20,6 +20,7 @@ struct Layout {
   float xscale;     // gamma * (alpha-1) * scale: Stage-1 score factor
   float pexp;       // 1/(alpha-1)
   bool use_mfma;    // bf16 prefill path (split summaries + MFMA Stage 1/2)
+  const int32_t* seq_lens;   // decode with per-sequence lengths: device array [batch], else null
   // workspace offsets in bytes (256-aligned); 0-sized regions share offsets
   size_t off_ksplit, off_mask, off_bias, off_scores, off_part, total;
 };
@@ -34,6 +35,8 @@ struct S1Out {
 
 hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const void* k, float* kbar,
                                 int first_chunk, int n_chunks, hipStream_t st);
+hipError_t launch_kbar_compress_completed(const dash_params& p, const Layout& L, const void* k, float* kbar,
+                                          hipStream_t st);
 hipError_t launch_kbar_summarize(const dash_params& p, const Layout& L, const void* k, const float* qbar,
                                  const int64_t* qs, float* kbar, int first_chunk, int n_chunks,
                                  hipStream_t st);

@@ -36,7 +36,8 @@ struct S1Args {
   int32_t* idx;
   float* bias;
   float* tau;
-  int batch, h_q, h_kv, g_q, n_q, block, t_c, t_all, words, pos0, causal, window, ld;
+  int batch, h_q, h_kv, g_q, n_q, n_kv, block, t_c, t_all, words, pos0, causal, window, ld;
+  const int32_t* seq_lens;   // decode with per-sequence lengths (device, [batch]) or null
   int64_t qs_b, qs_h, qs_t;
   float xscale, pexp, alpha, inv_sigma;
 };
@@ -358,6 +359,8 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
   const int r = hbi % a.h_kv, b = hbi / a.h_kv;
   const int tok0 = tile * tokt;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // per-sequence cache length (decode): query 0 of sequence b sits at len_b - n_q
+  if (a.seq_lens) a.pos0 = min(max(a.seq_lens[b], a.n_q), a.n_kv) - a.n_q;
   int n_cand = a.causal ? max((a.pos0 + tok0) / a.block - a.window, 0) : a.t_c;
   if (n_cand > a.t_c) n_cand = a.t_c;
 
@@ -526,10 +529,11 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void s1_scores_f32_kernel(
     const T* __restrict__ q, const float* __restrict__ kbar, float* __restrict__ scores, int h_q,
     int h_kv, int g_q, int n_q, int block, int t_c, int pos0, int causal, int64_t qs_b,
-    int64_t qs_h, int64_t qs_t, float xscale) {
+    int64_t qs_h, int64_t qs_t, float xscale, const int32_t* __restrict__ seq_lens, int n_kv) {
   constexpr int CPG = 4;                      // chunks per 16-lane group
   const int tok = blockIdx.y;
   const int b = blockIdx.z / h_kv, r = blockIdx.z % h_kv;
+  if (seq_lens) pos0 = min(max(seq_lens[b], n_q), n_kv) - n_q;   // per-sequence cache length (decode)
   int n_cand = causal ? (pos0 + tok) / block : t_c;
   if (n_cand > t_c) n_cand = t_c;
   const int c0 = blockIdx.x * 16 * CPG;
@@ -577,7 +581,7 @@ hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const voi
 #define DASH_SC(T_, D_)                                                                           \
   hipLaunchKernelGGL((s1_scores_f32_kernel<T_, D_>), grid, blk, 0, st, (const T_*)q, kbar, scores, \
                      p.h_q, p.h_kv, L.g_q, p.n_q, p.block_size, L.t_c, L.pos0, p.causal,          \
-                     p.q_stride[0], p.q_stride[1], p.q_stride[2], L.xscale)
+                     p.q_stride[0], p.q_stride[1], p.q_stride[2], L.xscale, L.seq_lens, p.n_kv)
   if (p.dtype == DASH_BF16) {
     if (p.head_dim == 128) DASH_SC(uint16_t, 128); else DASH_SC(uint16_t, 64);
   } else {
@@ -630,7 +634,8 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
   S1Args a;
   a.q = q; a.ksplit = ksplit; a.scores = scores;
   a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
-  a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.block = p.block_size;
+  a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv;
+  a.block = p.block_size; a.seq_lens = L.seq_lens;
   a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal; a.window = p.window;
   a.ld = ((L.t_c + 15) / 16) * 16 + 4;
   a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];

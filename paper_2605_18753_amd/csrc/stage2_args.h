@@ -13,6 +13,7 @@ struct S2Args {
   int64_t qs_b, qs_h, qs_t, ks_b, ks_h, ks_t, vs_b, vs_h, vs_t, os_b, os_h, os_t;
   float c1;      // scale * log2(e)
   float* part;   // decode partials
+  const int32_t* seq_lens;   // decode: per-sequence cache lengths (device, [batch]) or null
 };
 
 constexpr float kLazy = 8.f;   // lazy-rescale slack, in base-2 logit units
@@ -20,7 +21,7 @@ constexpr float kLazy = 8.f;   // lazy-rescale slack, in base-2 logit units
 inline void fill_s2_args(S2Args& a, const dash_params& p, const Layout& L, const void* q, const void* k,
                          const void* v, void* o, const uint32_t* mask, const float* bias) {
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.o = (uint16_t*)o;
-  a.mask = mask; a.bias = bias; a.part = nullptr;
+  a.mask = mask; a.bias = bias; a.part = nullptr; a.seq_lens = L.seq_lens;
   a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv;
   a.block = p.block_size; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0;
   a.causal = p.causal;

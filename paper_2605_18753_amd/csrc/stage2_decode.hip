@@ -62,7 +62,10 @@ __global__ __launch_bounds__(256, 3) void s2_decode_kernel(S2Args a) {
   const int pairs = a.hb, splits = a.n_tiles;
   const int pair = blockIdx.x % pairs, split = blockIdx.x / pairs;
   const int r = pair % a.h_kv, b = pair / a.h_kv;
-  const int pos = a.n_kv - 1;                 // the query's sequence position
+  // length of this sequence's cache (the current token included): the capacity
+  // n_kv, or the caller's per-sequence value, clamped to [1, n_kv]
+  const int len = a.seq_lens ? min(max(__builtin_amdgcn_readfirstlane(a.seq_lens[b]), 1), a.n_kv) : a.n_kv;
+  const int pos = len - 1;                    // the query's sequence position
   const int cw = pos / a.block;               // its (diagonal) chunk
   const int nsub = a.block >> 5;              // 32-key sub-tiles per chunk
 
@@ -129,8 +132,8 @@ __global__ __launch_bounds__(256, 3) void s2_decode_kernel(S2Args a) {
   }
 
   // ---- global -> LDS sub-tile copies (layout as in the prefill kernel) -------
-  const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
-  const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
+  const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)len - 1) * a.ks_t + D) * 2);
+  const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)len - 1) * a.vs_t + D) * 2);
   const uint32_t lds0 = lds_addr_of(lds);
   const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
   const uint32_t k_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ dk_swz<D>(c_row)) << 4));

@@ -197,6 +197,73 @@ def test_decode_updates_summary_cache_when_chunk_completes():
     U.check_against_oracle(w, q, k, v, run)
 
 
+@pytest.mark.parametrize("window,update", [(0, True), (1, True), (0, False)])
+def test_decode_ragged_lengths(window, update):
+    """One decode step over a batch whose sequences have different lengths in one cache
+    allocation: every sequence against the oracle run on its own prefix."""
+    cap, block, d, h_q, h_kv = 4096, 64, 128, 8, 2
+    lens = [3000, 64, 1025, 4096, 1, 2048]
+    w = Workload("decode_ragged", len(lens), h_q, h_kv, 1, cap, d, block, offset_sigma=0.7, seed=13, window=window)
+    q, k, v = gen(w)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, block, window=window)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    B.dash_kbar_compress(p, k, kbar)
+    good = kbar.clone()
+    # summaries a sequence must not read (its current chunk and everything after it) are poisoned;
+    # a chunk completed by the current token is the one the call itself has to write
+    for b, n in enumerate(lens):
+        kbar[b, :, (n - 1) // block:] = float("nan")
+    before = kbar.clone()
+    lists = B.Lists.allocate(p, DEV)
+    ws = B.alloc_workspace(p, DEV)
+    sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    B.dash_attn_decode_ragged(p, q, k, v, kbar, sl, o, lists, ws, update_cache=update)
+    torch.cuda.synchronize()
+    # cache maintenance: exactly the completed chunks were written, with the block mean
+    for b, n in enumerate(lens):
+        c = n // block - 1
+        if update and n % block == 0:
+            assert torch.equal(kbar[b, :, c], good[b, :, c])
+            before[b, :, c] = good[b, :, c]
+    assert torch.equal(torch.nan_to_num(kbar, nan=-7.0), torch.nan_to_num(before, nan=-7.0))
+    prm = U.oracle_params(w)
+    t_all = B.list_stride(p)
+    g = h_q // h_kv
+    rep = U.SupportReport()
+    worst = 0.0
+    for b, n in enumerate(lens):
+        for r in range(h_kv):
+            kn, vn = U.to_np(k[b, r, :n]), U.to_np(v[b, r, :n])
+            kb = orc.block_mean_summaries(kn, block)
+            qh = U.to_np(q[b, r * g:(r + 1) * g, 0])
+            rr = orc.dash_row_at(qh, kn, vn, kb, prm, n - 1, (b, r, 0))
+            U.compare_row(rr, w, lists.mask[b, r, 0].cpu().numpy(), int(lists.cnt[b, r, 0]),
+                          lists.idx[b, r, 0].cpu().numpy(), lists.bias[b, r, 0].cpu().numpy(),
+                          lists.tau[b, r * g:(r + 1) * g, 0].cpu().numpy(), rep, t_all)
+            got = U.to_np(o[b, r * g:(r + 1) * g, 0]).astype(np.float64)
+            worst = max(worst, np.abs(got - rr.o).max() / np.abs(rr.o).max())
+    assert rep.mismatched == 0 and rep.exempt <= 2
+    assert worst <= 2e-2, worst
+    print(f"ragged decode window={window}: sparsity {rep.sparsity:.3f} out_err {worst:.2e}")
+
+
+def test_decode_ragged_equals_uniform_decode_at_full_length():
+    w = Workload("decode_ragged_full", 3, 8, 2, 1, 2048, 128, 64, offset_sigma=0.7, seed=14)
+    q, k, v = gen(w)
+    ref = U.run_decode(w, q, k, v)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, 64)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    B.dash_kbar_compress(p, k, kbar)
+    lists = B.Lists.allocate(p, DEV)
+    ws = B.alloc_workspace(p, DEV)
+    sl = torch.full((3,), 2048, dtype=torch.int32, device=DEV)
+    B.dash_attn_decode_ragged(p, q, k, v, kbar, sl, o, lists, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o, ref.o) and torch.equal(lists.mask, ref.lists.mask) and torch.equal(lists.cnt, ref.lists.cnt)
+
+
 def test_split_stages_match_fused_call():
     w = Workload("stages", 1, 8, 2, 900, 900, 128, 64, seed=4)
     q, k, v = gen(w)

@@ -108,6 +108,21 @@ def test_summarize_argument_errors():
     assert lib.dash_kbar_compress(ctypes.byref(p), 256, 256, 15, 2, None) == -1
 
 
+def test_ragged_decode_argument_errors():
+    lib = B.load_library()
+    p = params(n_q=1, n_kv=4096)
+    need = B.workspace_bytes(p)
+    args = (256, 256, 256, 256)
+    assert lib.dash_attn_decode_ragged(ctypes.byref(p), *args, None, 1, 256, None, None, None, None, None,
+                                       256, need, None) == -1                            # no lengths
+    p32 = params(n_q=1, n_kv=4096, dtype=0)
+    assert lib.dash_attn_decode_ragged(ctypes.byref(p32), *args, 256, 1, 256, None, None, None, None, None,
+                                       256, 1 << 40, None) == -2                          # bf16 only
+    pq = params(n_q=64, n_kv=4096)
+    assert lib.dash_attn_decode_ragged(ctypes.byref(pq), *args, 256, 1, 256, None, None, None, None, None,
+                                       256, 1 << 40, None) == -1                          # one query per sequence
+
+
 def test_strerror():
     lib = B.load_library()
     assert lib.dash_strerror(0) == b"ok"
