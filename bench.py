@@ -160,7 +160,18 @@ def bench_decode(w, steps, warmup, torch, B, make_inputs):
                bytes_stage1=bytes_s1, kv_gbs=bytes_kv / (t * 1e-3) / 1e9,
                total_gbs=(bytes_kv + bytes_s1) / (t * 1e-3) / 1e9,
                dense_gbs=dense_bytes / (t_dense * 1e-3) / 1e9)
-    del q, k, v, o, od, ws, lists, kbar, kbar_l
+    # the same step over sequences of different lengths (a serving batch): lengths spread evenly
+    # between a quarter of the cache and the whole cache
+    lens = torch.linspace(w.n_kv // 4, w.n_kv, w.batch).to(torch.int32)
+    sl = lens.to(dev)
+    fr = lambda: B.dash_attn_decode_ragged(p, q, k, v, kbar, sl, o, lists, ws, update_cache=True)
+    fr()
+    torch.cuda.synchronize()
+    kept_r = float(lists.cnt.to(torch.int64).sum())
+    tr = timed(fr, steps, warmup, torch)
+    res["ragged"] = dict(us_step=tr * 1e3, mean_len=float(lens.float().mean()),
+                         kv_gbs=kept_r * w.block * w.head_dim * 2 * 2 / (tr * 1e-3) / 1e9)
+    del q, k, v, o, od, ws, lists, kbar
     torch.cuda.empty_cache()
     return res
 
@@ -371,7 +382,10 @@ def main():
                 **{name: {"gamma": g_, "us_per_step": r["us_step"], "dense_us_per_step": r["us_dense"],
                           "chunk_sparsity": r["sparsity"], "kv_GBps": r["kv_gbs"],
                           "kv_hbm_frac": r["kv_gbs"] / HBM_PEAK_GBS, "kv_plus_stage1_GBps": r["total_gbs"],
-                          "dense_GBps": r["dense_gbs"], "speedup_vs_dense": r["us_dense"] / r["us_step"]}
+                          "dense_GBps": r["dense_gbs"], "speedup_vs_dense": r["us_dense"] / r["us_step"],
+                          "ragged_lengths": {"us_per_step": r["ragged"]["us_step"],
+                                             "mean_length": r["ragged"]["mean_len"],
+                                             "kv_GBps": r["ragged"]["kv_gbs"]}}
                    for name, g_, r in (("gamma_1", 1.0, dec["gamma1"]), ("gamma_0.4", 0.4, dec["gamma04"]))},
             },
         },
