@@ -93,12 +93,15 @@ __global__ __launch_bounds__(256) void kbar_summarize_kernel(
     if constexpr (VEC == 8) return (double)((e & 1) ? bf16_hi(w[e >> 1]) : bf16_lo(w[e >> 1]));
     else return (double)__uint_as_float(w[e]);
   };
+  // all loads first, so that they are in flight together
+#pragma unroll
+  for (int i = 0; i < MAXR; i++)
+    if (i < nrow) raw[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)(r0 + i * rp) * ks_t);
   // scores s_t = <qbar, k_t> * scale: per-thread partial over its column group, then
   // a butterfly over the cg_n lanes that share the row
 #pragma unroll
   for (int i = 0; i < MAXR; i++) {
     if (i < nrow) {
-      raw[i] = *reinterpret_cast<const u32x4*>(base + (int64_t)(r0 + i * rp) * ks_t);
       double part = 0.0;
 #pragma unroll
       for (int e = 0; e < VEC; e++) part += qv[e] * key(raw[i], e);
@@ -107,12 +110,27 @@ __global__ __launch_bounds__(256) void kbar_summarize_kernel(
     }
   }
   __syncthreads();
-  double mx = sc[0];
-  for (int t = 1; t < block; t++) mx = fmax(mx, sc[t]);
-  if (threadIdx.x < block) ew[threadIdx.x] = exp(sc[threadIdx.x] - mx);
+  // softmax weights: thread t < block owns score t; maximum and sum by wave
+  // reductions plus one exchange through LDS (every thread ends up with the same
+  // values: the combination order is fixed)
+  __shared__ double red[8];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int nw = (block + 63) >> 6;            // waves that own scores (1 or 2)
+  double mine = threadIdx.x < block ? sc[threadIdx.x] : -INFINITY;
+  double wm = mine;
+  for (int m = 32; m >= 1; m >>= 1) wm = fmax(wm, __shfl_xor(wm, m));
+  if (lane == 0) red[wv] = wm;
   __syncthreads();
-  double den = 0.0;
-  for (int t = 0; t < block; t++) den += ew[t];
+  double mx = red[0];
+  for (int i = 1; i < nw; i++) mx = fmax(mx, red[i]);
+  const double ex = threadIdx.x < block ? exp(mine - mx) : 0.0;
+  if (threadIdx.x < block) ew[threadIdx.x] = ex;
+  double ws = ex;
+  for (int m = 32; m >= 1; m >>= 1) ws += __shfl_xor(ws, m);
+  if (lane == 0) red[4 + wv] = ws;
+  __syncthreads();
+  double den = red[4];
+  for (int i = 1; i < nw; i++) den += red[4 + i];
   double acc[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; e++) acc[e] = 0.0;
