@@ -264,6 +264,21 @@ def test_decode_ragged_equals_uniform_decode_at_full_length():
     assert torch.equal(o, ref.o) and torch.equal(lists.mask, ref.lists.mask) and torch.equal(lists.cnt, ref.lists.cnt)
 
 
+def test_stage1_token_ranges_do_not_change_the_result(monkeypatch):
+    """Long prefills run Stage 1 as several launches over token ranges; forcing that on a
+    short sequence must reproduce the single-launch lists bit for bit."""
+    w = Workload("s1_ranges", 2, 8, 2, 1500, 1500, 128, 64, seed=6, window=1)
+    q, k, v = gen(w)
+    monkeypatch.setenv("DASH_S1_SEGS", "1")
+    one = U.run_prefill(w, q, k, v)
+    for segs in ("3", "7"):
+        monkeypatch.setenv("DASH_S1_SEGS", segs)
+        many = U.run_prefill(w, q, k, v)
+        for name in ("mask", "cnt", "idx", "bias", "tau"):
+            assert torch.equal(getattr(one.lists, name), getattr(many.lists, name)), (segs, name)
+        assert torch.equal(one.o, many.o)
+
+
 def test_split_stages_match_fused_call():
     w = Workload("stages", 1, 8, 2, 900, 900, 128, 64, seed=4)
     q, k, v = gen(w)
