@@ -27,14 +27,14 @@ def to_np(t: torch.Tensor) -> np.ndarray:
 
 
 @dataclass
-class GpuRun:
+class HipRun:
     o: torch.Tensor
     kbar: torch.Tensor
     lists: B.Lists
     params: B.dash_params
 
 
-def run_prefill(w: Workload, q, k, v, *, want_idx=True) -> GpuRun:
+def run_prefill(w: Workload, q, k, v, *, want_idx=True) -> HipRun:
     dev = q.device
     o = torch.empty_like(q)
     p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal, window=w.window)
@@ -43,10 +43,10 @@ def run_prefill(w: Workload, q, k, v, *, want_idx=True) -> GpuRun:
     ws = B.alloc_workspace(p, dev)
     B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws)
     torch.cuda.synchronize()
-    return GpuRun(o, kbar, lists, p)
+    return HipRun(o, kbar, lists, p)
 
 
-def run_prefill_learned(w: Workload, q, k, v, qbar: torch.Tensor) -> GpuRun:
+def run_prefill_learned(w: Workload, q, k, v, qbar: torch.Tensor) -> HipRun:
     """The path with the learned Stage 0: summaries from dash_kbar_summarize, then
     the Stage-1 and Stage-2 entry points."""
     dev = q.device
@@ -59,7 +59,7 @@ def run_prefill_learned(w: Workload, q, k, v, qbar: torch.Tensor) -> GpuRun:
     B.dash_stage1_route(p, q, kbar, lists, ws)
     B.dash_stage2_attend(p, q, k, v, o, lists, ws)
     torch.cuda.synchronize()
-    return GpuRun(o, kbar, lists, p)
+    return HipRun(o, kbar, lists, p)
 
 
 def ulp_diff(a: np.ndarray, b: np.ndarray) -> np.ndarray:
@@ -70,7 +70,7 @@ def ulp_diff(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return np.abs(key(a) - key(b))
 
 
-def run_decode(w: Workload, q, k, v, kbar: Optional[torch.Tensor] = None) -> GpuRun:
+def run_decode(w: Workload, q, k, v, kbar: Optional[torch.Tensor] = None) -> HipRun:
     dev = q.device
     o = torch.empty_like(q)
     p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, True, window=w.window)
@@ -81,7 +81,7 @@ def run_decode(w: Workload, q, k, v, kbar: Optional[torch.Tensor] = None) -> Gpu
     ws = B.alloc_workspace(p, dev)
     B.dash_attn_decode(p, q, k, v, kbar, o, lists, ws)
     torch.cuda.synchronize()
-    return GpuRun(o, kbar, lists, p)
+    return HipRun(o, kbar, lists, p)
 
 
 def oracle_params(w: Workload) -> orc.DashParams:
@@ -180,7 +180,7 @@ def compare_row(rr: orc.RowResult, w: Workload, mask_words: np.ndarray, cnt: int
         assert err <= 2e-6, f"row {rr.b,rr.r,rr.iq}: tau {tau} vs {rr.tau}"
 
 
-def check_against_oracle(w: Workload, q, k, v, run: GpuRun,
+def check_against_oracle(w: Workload, q, k, v, run: HipRun,
                          rows: Optional[Sequence[Tuple[int, int, int]]] = None,
                          out_tol: Optional[float] = None, max_exempt_frac: float = 1e-3,
                          summaries=None):
