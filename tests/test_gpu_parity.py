@@ -328,6 +328,41 @@ def test_strided_layouts_decode():
     assert torch.equal(kbar, ref.kbar) and torch.equal(lists.mask, ref.lists.mask) and torch.equal(o, ref.o)
 
 
+def test_decode_step_replays_from_a_captured_graph():
+    """The entry points allocate nothing, never synchronise and enqueue only on the caller's
+    stream, so a decode step can be captured once and replayed: three replays with new queries
+    in the same buffers, with eager work and synchronisation in between, each equal to eager."""
+    w = Workload("decode_graph", 4, 8, 2, 1, 4096, 128, 64, offset_sigma=0.7, seed=17)
+    q, k, v = gen(w)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, 64)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    B.dash_kbar_compress(p, k, kbar)
+    lists = B.Lists.allocate(p, DEV)
+    ws = B.alloc_workspace(p, DEV)
+    B.dash_attn_decode(p, q, k, v, kbar, o, lists, ws)          # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.dash_attn_decode(p, q, k, v, kbar, o, lists, ws)
+    torch.cuda.synchronize()
+    gen_q = torch.Generator(device=DEV).manual_seed(3)
+    for rep in range(3):
+        q.copy_(torch.randn(q.shape, generator=gen_q, device=DEV).to(q.dtype))
+        o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got, got_mask = o.clone(), lists.mask.clone()
+        o.zero_()
+        B.dash_attn_decode(p, q, k, v, kbar, o, lists, ws)      # eager, same inputs
+        torch.cuda.synchronize()
+        assert torch.equal(got, o) and torch.equal(got_mask, lists.mask), rep
+        assert torch.isfinite(o.float()).all() and o.float().abs().max() > 0
+
+
 def test_split_stages_match_fused_call():
     w = Workload("stages", 1, 8, 2, 900, 900, 128, 64, seed=4)
     q, k, v = gen(w)
