@@ -347,10 +347,99 @@ __device__ __forceinline__ void emit_token(const float* S, const S1Args& a, uint
   __builtin_amdgcn_wave_barrier();
 }
 
+// The same emission by all four waves of the workgroup, for tiles that hold a single
+// token (decode; prefill at a GQA group of 16): wave w takes the 64-chunk slots
+// j = w, w + 4, ...; the ranks of a slot's members start at the number of members in
+// the slots below it, exchanged through LDS, as are the partial sums of ln w.  Same
+// arithmetic per chunk as emit_token; the sums are combined wave by wave, so mu may
+// differ from the single-wave order in the last place.
+template <int NJ>
+__device__ __forceinline__ void emit_token_wg(const float* S, const S1Args& a, uint32_t* mw, int* xcnt,
+                                              float* xsum, int tok, int n_cand, int lane, int wave,
+                                              int b, int r) {
+  constexpr int NW = NJ / 4;              // slots per wave
+  const float inv_g = 1.f / (float)a.g_q;
+  float lw[NW];
+  float slog = 0.f, nsup = 0.f;
+#pragma unroll
+  for (int jj = 0; jj < NW; jj++) {
+    const int c = lane + 64 * (wave + 4 * jj);
+    float s = 0.f;
+    if (c < n_cand)
+      for (int h = 0; h < a.g_q; h++) s += S[h * a.ld + c];
+    s *= inv_g;
+    lw[jj] = s > 0.f ? __builtin_amdgcn_logf(s) * 0.6931471805599453f : INFINITY;   // +inf marks "not routed"
+    if (s > 0.f) { slog += lw[jj]; nsup += 1.f; }
+  }
+  slog = wave_sum(slog);
+  nsup = wave_sum(nsup);
+  uint64_t bal[NW];
+#pragma unroll
+  for (int jj = 0; jj < NW; jj++) {
+    bal[jj] = __ballot(lw[jj] != INFINITY);
+    if (lane == 0) xcnt[wave + 4 * jj] = __popcll(bal[jj]);
+  }
+  if (lane == 0) { xsum[wave] = slog; xsum[4 + wave] = nsup; }
+  for (int wi = threadIdx.x; wi < a.words; wi += 256) mw[wi] = 0u;
+  __syncthreads();
+  const float slog_t = (xsum[0] + xsum[1]) + (xsum[2] + xsum[3]);
+  const float nsup_t = (xsum[4] + xsum[5]) + (xsum[6] + xsum[7]);
+  const float mu = nsup_t > 0.f ? slog_t / nsup_t : 0.f;
+  // members below each of this wave's slots: lane l holds the count of slot l
+  const int mine = lane < NJ ? xcnt[lane] : 0;
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 32; off <<= 1) {
+    const int t = __shfl_up(incl, off);
+    if (lane >= off) incl += t;
+  }
+  const int total = __shfl(incl, NJ - 1);
+  const int64_t base = ((int64_t)b * a.h_kv + r) * a.n_q + tok;
+  int32_t* oidx = a.idx ? a.idx + base * a.t_all : nullptr;
+  float* obias = a.bias + base * a.t_all;
+#pragma unroll
+  for (int jj = 0; jj < NW; jj++) {
+    const int j = wave + 4 * jj;
+    const int start = __shfl(incl - mine, j);
+    const int c = lane + 64 * j;
+    if (lane == 0 && 2 * j < a.words) {
+      mw[2 * j] = (uint32_t)bal[jj];
+      if (2 * j + 1 < a.words) mw[2 * j + 1] = (uint32_t)(bal[jj] >> 32);
+    }
+    if (lw[jj] != INFINITY) {
+      const int pos = start + __popcll(bal[jj] & ((1ull << lane) - 1ull));
+      if (oidx) oidx[pos] = c;
+      obias[pos] = (lw[jj] - mu) * a.inv_sigma;
+    }
+  }
+  __syncthreads();
+  int running = total;
+  if (a.causal) {
+    // the always-attended local set, bias 0: the chunks of the window, then the
+    // query's own chunk
+    const int cd = (a.pos0 + tok) / a.block;
+    const int c0 = max(cd - a.window, 0);
+    if (threadIdx.x == 0) {
+      for (int c = c0; c <= cd; c++) {
+        if (oidx) oidx[running + c - c0] = c;
+        obias[running + c - c0] = 0.f;
+        mw[c >> 5] |= 1u << (c & 31);
+      }
+    }
+    running += cd - c0 + 1;
+  }
+  __syncthreads();
+  if (a.cnt && threadIdx.x == 0) a.cnt[base] = running;
+  uint32_t* om = a.mask + base * a.words;
+  for (int wi = threadIdx.x; wi < a.words; wi += 256) om[wi] = mw[wi];
+}
+
 template <int MT, int D, bool FROM_MFMA>
 __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
   extern __shared__ float S[];   // [16*MT][ld] scores, then per-head probabilities
   __shared__ uint32_t mwords[4][64];
+  __shared__ int xcnt[32];
+  __shared__ float xsum[8];
   constexpr int ROWS = 16 * MT;
   const int tokt = ROWS / a.g_q;
   // workgroup id -> (tile, kv-head, batch), the (head, batch) pair fastest: the 8
@@ -464,6 +553,9 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
         const int tok = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
         const float* src = a.scores + (((int64_t)b * a.h_q + head) * a.n_q + (tok < a.n_q ? tok : 0)) * a.t_c;
         const bool ok = tok < a.tok_end;
+        // padding rows are zero-filled only where the solver reads them (the 16-lane-row
+        // solver takes four rows at a time; the wave-per-row solver stops at the first)
+        if (!ok && n_cand > 512) break;
         for (int c = lane; c < n_cand; c += 64) S[row * a.ld + c] = ok ? src[c] : 0.f;
       }
     }
@@ -510,6 +602,16 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
   }
   __syncthreads();
 
+  if (tokt == 1 || a.tok_end - tok0 <= 1) {
+    // one token in the tile (GQA group of 16, or a decode step): all four waves share
+    // its emission
+    if (tok0 >= a.tok_end) return;
+    if (nj <= 4) emit_token_wg<4>(S, a, mwords[0], xcnt, xsum, tok0, n_cand, lane, wave, b, r);
+    else if (nj <= 8) emit_token_wg<8>(S, a, mwords[0], xcnt, xsum, tok0, n_cand, lane, wave, b, r);
+    else if (nj <= 16) emit_token_wg<16>(S, a, mwords[0], xcnt, xsum, tok0, n_cand, lane, wave, b, r);
+    else emit_token_wg<32>(S, a, mwords[0], xcnt, xsum, tok0, n_cand, lane, wave, b, r);
+    return;
+  }
   for (int tl = wave; tl < tokt; tl += 4) {
     const int tok = tok0 + tl;
     if (tok >= a.tok_end) break;
