@@ -248,6 +248,61 @@ def test_decode_ragged_lengths(window, update):
     print(f"ragged decode window={window}: sparsity {rep.sparsity:.3f} out_err {worst:.2e}")
 
 
+@pytest.mark.parametrize("learned", [False, True])
+def test_decode_loop_over_growing_sequences(learned):
+    """A serving-shaped loop: four sequences of different lengths grow by one token per step and
+    cross chunk boundaries at different steps.  The summary cache starts with the chunks complete at
+    the start and is kept up to date either by the call (block mean) or by the caller (learned
+    summaries, update_cache = 0); every step is checked against the oracle on each sequence's prefix."""
+    cap, block, d, h_q, h_kv = 512, 64, 128, 8, 2
+    lens0 = [62, 127, 190, 300]
+    steps = 4
+    w = Workload("decode_loop", len(lens0), h_q, h_kv, 1, cap, d, block, offset_sigma=0.7, seed=19, window=1)
+    qs = [make_inputs(w.replace(seed=100 + s_), "cpu")[0].to(DEV) for s_ in range(steps)]
+    _, k, v = gen(w)
+    o = torch.empty_like(qs[0])
+    p = B.make_params(qs[0], k, v, o, block, window=1)
+    qbar = (torch.randn((h_kv, d), generator=torch.Generator().manual_seed(4)) * 2.0).float().to(DEV)
+    qn = qbar.cpu().numpy().astype(np.float64)[:, None, :]
+    kbar = torch.full(B.kbar_shape(p), float("nan"), dtype=torch.float32, device=DEV)
+    full = torch.empty_like(kbar)
+    if learned:
+        B.dash_kbar_summarize(p, k, qbar, full)
+    else:
+        B.dash_kbar_compress(p, k, full)
+    for b, n in enumerate(lens0):
+        kbar[b, :, : n // block] = full[b, :, : n // block]
+    lists = B.Lists.allocate(p, DEV)
+    ws = B.alloc_workspace(p, DEV)
+    prm = U.oracle_params(w)
+    g = h_q // h_kv
+    for s_ in range(steps):
+        lens = [n + s_ + 1 for n in lens0]                     # the current token is already in the cache
+        sl = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        if learned:                                            # the caller maintains the cache
+            for b, n in enumerate(lens):
+                if n % block == 0:
+                    pb = B.make_params(qs[s_][b:b + 1], k[b:b + 1], v[b:b + 1], None, block)
+                    B.dash_kbar_summarize(pb, k[b:b + 1], qbar, kbar[b:b + 1], n // block - 1, 1)
+        B.dash_attn_decode_ragged(p, qs[s_], k, v, kbar, sl, o, lists, ws, update_cache=not learned)
+        torch.cuda.synchronize()
+        rep = U.SupportReport()
+        for b, n in enumerate(lens):
+            assert torch.equal(kbar[b, :, : n // block], full[b, :, : n // block])      # complete chunks are in
+            assert torch.isnan(kbar[b, :, n // block:]).all()                            # nothing else was touched
+            for r in range(h_kv):
+                kn, vn = U.to_np(k[b, r, :n]), U.to_np(v[b, r, :n])
+                kb = orc.local_attention_summaries(kn, qn[r], block) if learned else orc.block_mean_summaries(kn, block)
+                qh = U.to_np(qs[s_][b, r * g:(r + 1) * g, 0])
+                rr = orc.dash_row_at(qh, kn, vn, kb, prm, n - 1, (b, r, 0))
+                U.compare_row(rr, w, lists.mask[b, r, 0].cpu().numpy(), int(lists.cnt[b, r, 0]),
+                              lists.idx[b, r, 0].cpu().numpy(), lists.bias[b, r, 0].cpu().numpy(),
+                              lists.tau[b, r * g:(r + 1) * g, 0].cpu().numpy(), rep, B.list_stride(p))
+                got = U.to_np(o[b, r * g:(r + 1) * g, 0]).astype(np.float64)
+                assert np.abs(got - rr.o).max() / np.abs(rr.o).max() <= 2e-2, (s_, b, r)
+        assert rep.mismatched == 0 and rep.exempt <= 1
+
+
 def test_decode_ragged_equals_uniform_decode_at_full_length():
     w = Workload("decode_ragged_full", 3, 8, 2, 1, 2048, 128, 64, offset_sigma=0.7, seed=14)
     q, k, v = gen(w)
