@@ -334,6 +334,33 @@ def test_stage1_token_ranges_do_not_change_the_result(monkeypatch):
         assert torch.equal(one.o, many.o)
 
 
+def test_rising_logits_exercise_the_rescale_path():
+    """Keys whose norm grows along the sequence and sharp queries: the running maximum of the online
+    softmax keeps rising, so the (normally rare) rescale of the accumulators runs many times per row,
+    in the routed prefill, the dense kernel and the decode kernel."""
+    w = Workload("rising", 1, 8, 2, 1536, 1536, 128, 64, seed=21, offset_sigma=0.3)
+    q, k, v = gen(w)
+    ramp = (1.0 + 3.0 * torch.arange(w.n_kv, device=DEV) / w.n_kv).view(1, 1, -1, 1)
+    k = (k.float() * ramp).to(k.dtype)
+    q = (q.float() * 3.0).to(q.dtype)
+    run = U.run_prefill(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96))
+    print(f"rising prefill: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    o = torch.empty_like(q)
+    B.dense_attn(run.params, q, k, v, o, B.alloc_workspace(run.params, DEV))
+    torch.cuda.synchronize()
+    qn, kn, vn = U.to_np(q), U.to_np(k), U.to_np(v)
+    for h in (0, 5):
+        ref = orc.dense_attention(qn[0, h], kn[0, h // 4], vn[0, h // 4], 1.0 / np.sqrt(128.0), True)
+        assert np.abs(U.to_np(o)[0, h] - ref).max() / np.abs(ref).max() <= 2e-2
+    wd = Workload("rising_decode", 2, 8, 2, 1, 1536, 128, 64, seed=22, offset_sigma=0.3)
+    qd, kd, vd = gen(wd)
+    kd = (kd.float() * ramp).to(kd.dtype)
+    qd = (qd.float() * 3.0).to(qd.dtype)
+    rund = U.run_decode(wd, qd, kd, vd)
+    U.check_against_oracle(wd, qd, kd, vd, rund)
+
+
 def _token_major(t):
     """The same values stored [batch, token, head, d] (the layout of a fused QKV projection),
     viewed as [batch, head, token, d]: head and token strides are swapped, d stays contiguous."""
