@@ -361,6 +361,30 @@ def test_rising_logits_exercise_the_rescale_path():
     U.check_against_oracle(wd, qd, kd, vd, rund)
 
 
+@pytest.mark.parametrize("dtype,h_q,h_kv,n_q,n_kv,d,block", [
+    ("bf16", 8, 2, 512, 1536, 128, 64), ("bf16", 16, 1, 384, 1000 + 24, 64, 128), ("fp32", 4, 2, 192, 640, 64, 64)])
+def test_chunked_prefill_continues_a_longer_cache(dtype, h_q, h_kv, n_q, n_kv, d, block):
+    """Prefill of the last n_q tokens against a cache of n_kv keys (the queries sit at positions
+    n_kv - n_q .. n_kv - 1): every row against the oracle, and equal to the same rows of one
+    prefill over the whole sequence."""
+    w = Workload("chunked", 1, h_q, h_kv, n_q, n_kv, d, block, dtype=dtype, seed=23, window=1, offset_sigma=1.2,
+                 alpha=2.0 if d == 64 else 1.5)
+    q, k, v = gen(w)
+    run = U.run_prefill(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run)
+    print(f"chunked prefill {dtype}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    # the same rows as part of a full-length prefill (queries for the earlier positions are arbitrary)
+    wf = w.replace(n_q=n_kv)
+    qf = torch.zeros((1, h_q, n_kv, d), dtype=q.dtype, device=DEV)
+    qf[:, :, n_kv - n_q:] = q
+    full = U.run_prefill(wf, qf, k, v)
+    assert torch.equal(full.lists.mask[:, :, n_kv - n_q:], run.lists.mask)
+    assert torch.equal(full.lists.cnt[:, :, n_kv - n_q:], run.lists.cnt)
+    tol = 2e-2 if dtype == "bf16" else 1e-5
+    diff = (full.o[:, :, n_kv - n_q:].float() - run.o.float()).abs().max() / run.o.float().abs().max()
+    assert diff <= tol, diff
+
+
 def _token_major(t):
     """The same values stored [batch, token, head, d] (the layout of a fused QKV projection),
     viewed as [batch, head, token, d]: head and token strides are swapped, d stays contiguous."""
