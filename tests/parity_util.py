@@ -111,15 +111,28 @@ def mask_bits(words: np.ndarray, n_bits: int) -> np.ndarray:
     return bits[:n_bits]
 
 
-def mu_error_bound(rr: orc.RowResult) -> float:
-    """Bound on the fp32 error of mu = mean_R ln w.  A routed chunk whose largest
-    head margin u = x - tau is small has an ill-conditioned ln w: an fp32 error
-    eps ~ 1e-6 (generous) in the margin moves ln w by ~ 2 eps / u (alpha = 1.5; less for
-    alpha = 2), and mu by the mean of that over the routed set."""
+def lnw_error_bound(rr: orc.RowResult, alpha: float) -> np.ndarray:
+    """Per candidate chunk, a bound on the fp32 error of ln w, where
+    w = mean_h [x_h - tau_h]_+^p and p = 1/(alpha-1) (Eq. 4 with the group mean
+    of Sec. 3.3).  An fp32 error eps ~ 1e-6 (generous) in each head's margin
+    u_h = x_h - tau_h moves ln w by eps * sum_h p u_h^(p-1) / sum_h u_h^p.  For
+    p >= 1 the largest margin dominates (about p eps / u_max); for p < 1 a head
+    that keeps the chunk by a hair contributes the most."""
+    p = 1.0 / (alpha - 1.0)
+    u = np.maximum(rr.x - rr.tau[:, None], 0.0)               # [g_q, n_cand]
+    pos = u > 0
+    uf = np.where(pos, np.maximum(u, 1e-9), 1.0)
+    num = np.where(pos, p * uf ** (p - 1.0), 0.0).sum(axis=0)
+    den = np.where(pos, uf ** p, 0.0).sum(axis=0)
+    return 1e-6 * num / np.maximum(den, 1e-300)
+
+
+def mu_error_bound(rr: orc.RowResult, alpha: float) -> float:
+    """Bound on the fp32 error of mu = mean_R ln w: the mean of the routed
+    chunks' ln w bounds."""
     if rr.routed.size == 0:
         return 0.0
-    umax = (rr.x - rr.tau[:, None]).max(axis=0)[rr.routed]
-    return float(np.mean(2e-6 / np.maximum(umax, 1e-9)))
+    return float(np.mean(lnw_error_bound(rr, alpha)[rr.routed]))
 
 
 def compare_row(rr: orc.RowResult, w: Workload, mask_words: np.ndarray, cnt: int,
@@ -167,17 +180,18 @@ def compare_row(rr: orc.RowResult, w: Workload, mask_words: np.ndarray, cnt: int
     if not diff and len(ref_set):
         order = sorted(gpu_set)
         ref_bias = dict(zip(rr.routed.tolist(), rr.bias.tolist()))
-        umax = (rr.x - rr.tau[:, None]).max(axis=0)
-        mu_slack = mu_error_bound(rr)
+        lnw_slack = lnw_error_bound(rr, w.alpha)
+        mu_slack = mu_error_bound(rr, w.alpha)
         for j, c in enumerate(order):
-            tol = (2e-4 + 2e-6 / max(umax[c], 1e-9) + mu_slack) / w.sigma + 1e-6 * abs(ref_bias[c])
+            tol = (2e-4 + lnw_slack[c] + mu_slack) / w.sigma + 1e-6 * abs(ref_bias[c])
             err = abs(bias[j] - ref_bias[c])
             rep.worst_bias_err = max(rep.worst_bias_err, err * w.sigma)
             assert err <= tol, f"row {rr.b,rr.r,rr.iq} chunk {c}: bias {bias[j]} vs {ref_bias[c]}"
     if tau is not None and rr.n_cand:
         err = float(np.abs(tau - rr.tau).max())
         rep.worst_tau_err = max(rep.worst_tau_err, err)
-        assert err <= 2e-6, f"row {rr.b,rr.r,rr.iq}: tau {tau} vs {rr.tau}"
+        # fp32 scores and thresholds: a few ulp of the largest magnitude in the row
+        assert err <= 2e-6 * max(1.0, float(np.abs(rr.x).max())), f"row {rr.b,rr.r,rr.iq}: tau {tau} vs {rr.tau}"
 
 
 def check_against_oracle(w: Workload, q, k, v, run: HipRun,
@@ -227,7 +241,7 @@ def check_against_oracle(w: Workload, q, k, v, run: HipRun,
         # causal rows: an error in mu shifts mass between the routed and the
         # diagonal branch by at most that error (non-causal: it cancels)
         if w.causal:
-            slack[n] = mu_error_bound(rr) / w.sigma
+            slack[n] = mu_error_bound(rr, w.alpha) / w.sigma
     assert rep.mismatched == 0, f"{rep.mismatched} support mismatches outside the 1e-6 band"
     assert rep.exempt <= max(2, max_exempt_frac * rep.blocks), f"too many exempt chunks: {rep.exempt}"
     tol = out_tol if out_tol is not None else (2e-2 if w.dtype == "bf16" else 1e-5)

@@ -125,6 +125,15 @@ SMALL = [
     ("window1_gqa4", 1, 8, 2, 1000, 128, 64, {"window": 1}),
     ("window2_gqa8_b128_d64", 1, 8, 1, 1536, 64, 128, {"window": 2, "offset_sigma": 1.0}),
     ("window1_one_chunk_only", 1, 4, 1, 100, 128, 64, {"window": 1}),
+    # corners of the parameter space: alpha close to 1 (near softmax, large exponent) and far above 2
+    # (exponent 1/3), weak and strong logit scaling, a very sharp and a vanishing prior
+    ("alpha105", 1, 8, 2, 1100, 128, 64, {"alpha": 1.05, "offset_sigma": 0.8}),
+    ("alpha4_bisect", 1, 8, 2, 1100, 128, 64, {"alpha": 4.0, "offset_sigma": 0.8}),
+    ("gamma005", 1, 8, 2, 1100, 128, 64, {"gamma": 0.05, "offset_sigma": 0.8}),
+    ("gamma4", 1, 8, 2, 1100, 128, 64, {"gamma": 4.0, "offset_sigma": 0.8}),
+    ("sigma01", 1, 8, 2, 1100, 128, 64, {"sigma": 0.1, "offset_sigma": 0.8}),
+    ("alpha2_gamma3_sigma1e8", 1, 8, 2, 1100, 128, 64, {"alpha": 2.0, "gamma": 3.0, "sigma": 1e8,
+                                                         "offset_sigma": 0.8}),
 ]
 
 
