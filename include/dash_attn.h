@@ -1,7 +1,8 @@
 /*
- * dash_attn.h -- C ABI of the MI355X (gfx950) DashAttention forward library.
+ * dash_attn.h -- C ABI of the MI355X (gfx950) DashAttention library.
  *
- * The library implements the forward hot path of DashAttention:
+ * The library implements the forward hot path of DashAttention (and the backward
+ * pass of its prefill path, dash_attn_backward):
  *   Stage 0  block-mean key summaries                     (Sec. 3.1, Eq. 3 at a zero
  *                                                          summary query; Alg. 1)
  *   Stage 1  entmax chunk routing per query, GQA averaged  (Sec. 3.2, Eq. 4; Alg. 2)
@@ -195,6 +196,34 @@ int dash_attn_decode_ragged(const dash_params* p, const void* q, const void* k_c
  * ignored except for validation. */
 int dense_attn(const dash_params* p, const void* q, const void* k, const void* v,
                void* o, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of dash_attn_prefill (end of Sec. 3.3: the output is differentiable in
+ * q, k, v and the prior, and the gradient reaches the Stage-1 weights and the
+ * Stage-0 summaries; Sec. 3.5: the backward pass reuses the forward's chunk mask,
+ * the entmax Jacobian being zero outside the support).  Within the forward's
+ * support the gradient is exact; at a support change the map is only piecewise
+ * differentiable and the Jacobian of the current support is used.
+ *   q, k, v        in  the forward's inputs (same dash_params)
+ *   d_o            in  gradient of the loss with respect to the forward's output o,
+ *                  layout and strides of o (o itself is not needed: <dO, o> is
+ *                  recomputed in fp32)
+ *   kbar           in  the block-mean summaries the forward wrote (fp32)
+ *   mask, blk_bias, tau  in  the forward's Stage-1 outputs (all three required)
+ *   dq, dk, dv     out gradients in the run dtype with the strides of q, k, v;
+ *                  dk includes the path through the routing scores into the block
+ *                  means (each key of a complete chunk receives 1/B of the
+ *                  chunk summary's gradient); every element is written
+ *   workspace      device scratch of dash_attn_backward_workspace_bytes bytes,
+ *                  256-byte aligned (separate from, or reusing, the forward's)
+ * bf16, n_q == n_kv and block-mean summaries only (DASH_EUNSUPPORTED otherwise,
+ * also when a (batch, kv-head) slice of a tensor spans 2 GiB or more);
+ * DASH_EINVAL for a NULL pointer. */
+int dash_attn_backward_workspace_bytes(const dash_params* p, size_t* out_bytes);
+int dash_attn_backward(const dash_params* p, const void* q, const void* k, const void* v,
+                       const void* d_o, const float* kbar,
+                       const uint32_t* mask, const float* blk_bias, const float* tau,
+                       void* dq, void* dk, void* dv,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* Static, NUL-terminated description of a dash_status. */
 const char* dash_strerror(int code);

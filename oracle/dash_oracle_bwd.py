@@ -65,11 +65,18 @@ def entmax_jacobian_vjp(x: np.ndarray, tau: float, alpha: float, dw: np.ndarray)
 
 
 def backward_row(qh: np.ndarray, k: np.ndarray, v: np.ndarray, kbar: np.ndarray, d_o: np.ndarray,
-                 prm: orc.DashParams, pos: int, dk: np.ndarray, dv: np.ndarray, dkbar: np.ndarray):
+                 prm: orc.DashParams, pos: int, dk: np.ndarray, dv: np.ndarray, dkbar: np.ndarray,
+                 margin_shift: float = 0.0):
     """Backward of dash_oracle.dash_row_at for the g_q heads qh [g_q, d] at
     position pos with upstream gradient d_o [g_q, d].  Adds this row's
     contributions into dk, dv [n_kv, d] and dkbar [T_c, d]; returns
-    (dq [g_q, d], dx [g_q, n_cand], dd [len(routed)])."""
+    (dq [g_q, d], dx [g_q, n_cand], dd [len(routed)]).
+
+    margin_shift (a test aid, 0 for the gradient itself) evaluates the prior and
+    the entmax Jacobian with every margin x - tau moved by that amount, the
+    support kept: the change of the result measures how an error of that size in
+    a lower-precision evaluation of the scores propagates (ln w and 1/w are
+    singular at the edge of the support)."""
     qh = np.asarray(qh, dtype=np.float64)
     d_o = np.asarray(d_o, dtype=np.float64)
     g_q, d = qh.shape
@@ -107,18 +114,25 @@ def backward_row(qh: np.ndarray, k: np.ndarray, v: np.ndarray, kbar: np.ndarray,
     dx = np.zeros((g_q, rr.n_cand))
     if len(rr.routed):
         dlnw = (dd - dd.mean()) / prm.sigma
+        w_used = rr.w
+        x_used = rr.x
+        if margin_shift != 0.0:
+            p = 1.0 / (prm.alpha - 1.0)
+            sup = rr.x > rr.tau[:, None]
+            x_used = np.where(sup, np.maximum(rr.x + margin_shift, rr.tau[:, None] + 1e-12), rr.x)
+            w_used = (np.where(sup, x_used - rr.tau[:, None], 0.0) ** p).sum(axis=0) / float(g_q)
         dw = np.zeros(rr.n_cand)
-        dw[rr.routed] = dlnw / rr.w[rr.routed]
+        dw[rr.routed] = dlnw / w_used[rr.routed]
         c_x = prm.gamma * (prm.alpha - 1.0) * scale
         for h in range(g_q):
-            dx[h] = entmax_jacobian_vjp(rr.x[h], rr.tau[h], prm.alpha, dw / float(g_q))
+            dx[h] = entmax_jacobian_vjp(x_used[h], rr.tau[h], prm.alpha, dw / float(g_q))
             dq[h] += c_x * (dx[h] @ np.asarray(kbar[:rr.n_cand], dtype=np.float64))
             dkbar[:rr.n_cand] += c_x * np.outer(dx[h], qh[h])
     return dq, dx, dd
 
 
 def dash_backward_group(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.ndarray,
-                        prm: orc.DashParams, kbar: Optional[np.ndarray] = None
+                        prm: orc.DashParams, kbar: Optional[np.ndarray] = None, margin_shift: float = 0.0
                         ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
     """Backward for one (batch, kv-head) pair: q, d_o [g_q, n_q, d]; k, v
     [n_kv, d]; query t sits at position n_kv - n_q + t.  kbar None: block-mean
@@ -138,7 +152,8 @@ def dash_backward_group(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.nda
     dv = np.zeros_like(v)
     dkbar = np.zeros_like(np.asarray(kbar, dtype=np.float64))
     for t in range(n_q):
-        dq[:, t], _, _ = backward_row(q[:, t], k, v, kbar, d_o[:, t], prm, n_kv - n_q + t, dk, dv, dkbar)
+        dq[:, t], _, _ = backward_row(q[:, t], k, v, kbar, d_o[:, t], prm, n_kv - n_q + t, dk, dv, dkbar,
+                                      margin_shift)
     if fold:
         blk = prm.block
         for c in range(dkbar.shape[0]):

@@ -54,6 +54,8 @@ _SIGNATURES = {
     "dash_attn_decode_ragged": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_int32, _V, _V, _V, _V, _V, _V, _V,
                                                ctypes.c_size_t, _V]),
     "dense_attn": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
+    "dash_attn_backward_workspace_bytes": (ctypes.c_int, [_P, ctypes.POINTER(ctypes.c_size_t)]),
+    "dash_attn_backward": (ctypes.c_int, [_P] + [_V] * 12 + [ctypes.c_size_t, _V]),
     "dash_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
 
@@ -225,6 +227,26 @@ def dense_attn(p, q, k, v, o, ws: torch.Tensor) -> None:
     wp, wn = _ws_ptr(ws)
     _check(load_library().dense_attn(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(o), wp, wn, _stream()),
            "dense_attn")
+
+
+def backward_workspace_bytes(p: dash_params) -> int:
+    n = ctypes.c_size_t(0)
+    _check(load_library().dash_attn_backward_workspace_bytes(ctypes.byref(p), ctypes.byref(n)),
+           "dash_attn_backward_workspace_bytes")
+    return n.value
+
+
+def alloc_backward_workspace(p: dash_params, device) -> torch.Tensor:
+    return torch.empty(backward_workspace_bytes(p) + 256, dtype=torch.uint8, device=device)
+
+
+def dash_attn_backward(p, q, k, v, d_o, kbar, lists: Lists, dq, dk, dv, ws: torch.Tensor) -> None:
+    """Backward of dash_attn_prefill; lists.mask / bias / tau are the forward's outputs."""
+    wp, wn = _ws_ptr(ws)
+    _check(load_library().dash_attn_backward(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(d_o),
+                                             _ptr(kbar), _ptr(lists.mask), _ptr(lists.bias), _ptr(lists.tau),
+                                             _ptr(dq), _ptr(dk), _ptr(dv), wp, wn, _stream()),
+           "dash_attn_backward")
 
 
 def kbar_shape(p: dash_params):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdash_attn.so")
-SOURCES = ["api.hip", "compress.hip", "stage1.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip"]
+SOURCES = ["api.hip", "compress.hip", "stage1.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip", "backward.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -258,6 +258,45 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
   return run_stage2(p, L, q, k, v, o, nullptr, nullptr, (char*)workspace, true, (hipStream_t)stream);
 }
 
+static int backward_layout(const dash_params* p, Layout* L) {
+  int rc = make_layout(p, L);
+  if (rc != DASH_OK) return rc;
+  if (p->dtype != DASH_BF16 || p->n_q != p->n_kv) return DASH_EUNSUPPORTED;
+  // the kernels address a (batch, kv-head) slice of every tensor with 32-bit byte offsets
+  const int64_t lim = (int64_t)1 << 31;
+  const int64_t g = L->g_q, n = p->n_q, d = p->head_dim;
+  if (((g - 1) * p->q_stride[1] + (n - 1) * p->q_stride[2] + d) * 2 >= lim ||
+      ((g - 1) * p->o_stride[1] + (n - 1) * p->o_stride[2] + d) * 2 >= lim ||
+      ((n - 1) * p->k_stride[2] + d) * 2 >= lim || ((n - 1) * p->v_stride[2] + d) * 2 >= lim)
+    return DASH_EUNSUPPORTED;
+  return DASH_OK;
+}
+
+int dash_attn_backward_workspace_bytes(const dash_params* p, size_t* out_bytes) {
+  if (!out_bytes) return DASH_EINVAL;
+  Layout L;
+  const int rc = backward_layout(p, &L);
+  if (rc != DASH_OK) return rc;
+  *out_bytes = backward_workspace_bytes(*p, L);
+  return DASH_OK;
+}
+
+int dash_attn_backward(const dash_params* p, const void* q, const void* k, const void* v,
+                       const void* d_o, const float* kbar, const uint32_t* mask, const float* blk_bias,
+                       const float* tau, void* dq, void* dk, void* dv, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  Layout L;
+  const int rc = backward_layout(p, &L);
+  if (rc != DASH_OK) return rc;
+  if (!q || !k || !v || !d_o || !mask || !blk_bias || !tau || !dq || !dk || !dv ||
+      (!kbar && L.t_c > 0))
+    return DASH_EINVAL;
+  if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < backward_workspace_bytes(*p, L))
+    return DASH_EWORKSPACE;
+  return launch_backward(*p, L, q, k, v, d_o, kbar, mask, blk_bias, tau, dq, dk, dv, (char*)workspace,
+                         (hipStream_t)stream) == hipSuccess ? DASH_OK : DASH_ELAUNCH;
+}
+
 const char* dash_strerror(int code) {
   switch (code) {
     case DASH_OK: return "ok";

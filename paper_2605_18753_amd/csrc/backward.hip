@@ -1,0 +1,839 @@
+// Backward pass of the prefill path (bf16): gradients of the block-sparse
+// attention with the routing prior with respect to q, k and v, including the
+// path through the bias into the Stage-1 entmax weights and from there into the
+// block-mean summaries (end of Sec. 3.3: the output is differentiable in q, k, v
+// and the prior, so the gradient reaches Stage 1 and Stage 0; Sec. 3.5: the
+// backward pass reuses the forward's chunk mask because the entmax Jacobian is
+// zero outside the support).
+//
+// With P = softmax(z + d) over the attended tokens (z = q.k scale, d the bias
+// of the token's chunk, 0 on the local chunks), o = P V and upstream dO:
+//   dP = V dO,  D = <P, dP> (= <dO, o>),  dz = P (dP - D)
+//   dq = scale K^T dz,  dK = scale dz q^T,  dV = P dO^T
+//   dd_c = sum over the group's heads and the chunk's tokens of dz
+//   dlnw_c = (dd_c - mean_R dd) / sigma,  dw_c = dlnw_c / w_c,  dw_hat = dw / g_q
+//   dx_{h,c} = g_{h,c} (dw_hat_c - sum_j g_{h,j} dw_hat_j / sum_j g_{h,j}),
+//       g_{h,c} = p u^(p-1) on the head's support, u = x - tau, p = 1/(alpha-1)
+//   dq_h += c sum_c dx_{h,c} kbar_c,  dkbar_c = c sum_{rows} dx q,  c = gamma (alpha-1) scale
+//   dK_j += dkbar_c / B for the keys of a complete chunk c (block mean).
+//
+// Three kernels:
+//   bwd_q_kernel   owns 128 (token, head) rows like the forward kernel and walks the
+//                  union of their chunks twice: first for the row log-sum-exp and D,
+//                  then for dq (attention part, fp32), dd and a dense copy of the
+//                  bias; it also marks, per chunk, which row tiles attend it.
+//   bwd_route_kernel  one wave per (kv-head, token): prior and entmax Jacobian,
+//                  dx per head and chunk, the routing part of dq, final dq.
+//   bwd_kv_kernel  owns a 64-key tile, walks the row tiles that attend its chunk and
+//                  accumulates dK, dV and the chunk's dkbar without atomics.
+// MFMA operand layouts are those of the forward kernel: every product is
+// arranged so that the accumulator of the first product is directly the
+// B operand of the second; the transposed operand comes from LDS through the
+// transposing read.
+#include <math.h>
+#include <stdlib.h>
+
+#include "common.h"
+#include "dash_internal.h"
+#include "lds_copy.h"
+
+namespace dash {
+
+struct BwdArgs {
+  const uint16_t *q, *k, *v, *d_o;
+  uint16_t *dq, *dk, *dv;
+  const float* kbar; const uint32_t* mask; const float* bias; const float* tau;
+  float *lse, *dsum;       // [batch, h_q, n_q]: base-2 log-sum-exp of the logits, <dO, o>
+  float *biasd, *dbd;      // [batch, h_kv, n_q, t_all]: bias and its gradient by chunk id
+  float* dxd;              // [batch, h_q, n_q, t_all]: entmax-score gradient by chunk id
+  float* dq32;             // [batch, h_q, n_q, D]: attention part of dq
+  uint32_t* colmask;       // [batch*h_kv, t_all, cwords]: bit T set iff row tile T attends the chunk
+  int h_q, h_kv, g_q, n_q, n_kv, block, t_c, t_all, words, causal, window, n_tiles, hb, cwords;
+  int64_t qs_b, qs_h, qs_t, ks_b, ks_h, ks_t, vs_b, vs_h, vs_t, os_b, os_h, os_t;
+  float c1, scale, xscale, pexp, sigma;
+};
+
+template <int D> struct BCfg {
+  static constexpr int NCH = D / 8;
+  static constexpr int ROW_BYTES = D * 2;
+  static constexpr int TILE_BYTES = 64 * ROW_BYTES;
+  static constexpr int COPIES = TILE_BYTES / 16 / 256;
+  static constexpr int ROWS_PER_COPY = 256 / NCH;
+  static constexpr int NDT = D / 32;
+  static constexpr int NS = D / 8;
+};
+
+// chunk permutations of a 64-row tile: `a` for rows read as an MFMA A operand,
+// `t` for rows read through the transposing read (same choices as the forward)
+template <int D> __device__ __forceinline__ int swz_a(int row) {
+  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+}
+template <int D> __device__ __forceinline__ int swz_t(int row) {
+  return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+}
+
+// A operand slice `i` (d slice i / 2, 32-row half i % 2) of a row-major tile
+template <int D> __device__ __forceinline__ bf16x8 read_a(const char* tile, const uint32_t* rd, int i) {
+  return *reinterpret_cast<const bf16x8*>(tile + rd[i >> 1] + (i & 1) * 32 * BCfg<D>::ROW_BYTES);
+}
+// transposed A operand: contraction step g (16 tile rows), d-tile t
+template <int D> __device__ __forceinline__ bf16x8 read_t(const char* tile, const uint32_t* rd, int g, int t) {
+  return lds_read_tr_pair(tile + rd[t] + (16 * g) * BCfg<D>::ROW_BYTES,
+                          tile + rd[t] + (16 * g + 8) * BCfg<D>::ROW_BYTES);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+  const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  return z;
+}
+
+__global__ void bwd_fill_zero_kernel(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// Row-owner kernel.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_q_kernel(BwdArgs a) {
+  using C = BCfg<D>;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* ka_t = lds;                           // K, A-operand layout
+  char* kt_t = lds + C::TILE_BYTES;           // K, transposing-read layout
+  char* va_t = lds + 2 * C::TILE_BYTES;       // V, A-operand layout
+  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + 3 * C::TILE_BYTES);   // [64]
+  uint32_t* wvmask = wgmask + 64;                                            // [4][64]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const int hbi = blockIdx.x % a.hb;
+  const int tile = a.n_tiles - 1 - blockIdx.x / a.hb;
+  const int r = hbi % a.h_kv, b = hbi / a.h_kv;
+  const int tokw = 32 / a.g_q;
+  const int tok_w0 = tile * 4 * tokw + wave * tokw;
+  const int nsub = a.block >> 6;
+
+  const int my_tok = tok_w0 + n / a.g_q;
+  const int my_head = r * a.g_q + n % a.g_q;
+  const bool row_ok = my_tok < a.n_q;
+  const int row_tok = row_ok ? my_tok : a.n_q - 1;
+  const int row_pos = row_tok;                                   // n_q == n_kv
+  const int cw = (tok_w0 < a.n_q ? tok_w0 : a.n_q - 1) / a.block;
+  const bool wave_ok = tok_w0 < a.n_q;
+
+  // ---- row fragments: q and dO as B operands -------------------------------------
+  bf16x8 qf[D / 16], dof[D / 16];
+  {
+    const uint16_t* qp = a.q + b * a.qs_b + my_head * a.qs_h + (int64_t)row_tok * a.qs_t + h * 8;
+    const uint16_t* dop = a.d_o + b * a.os_b + my_head * a.os_h + (int64_t)row_tok * a.os_t + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+      dof[ks] = *reinterpret_cast<const bf16x8*>(dop + ks * 16);
+    }
+  }
+
+  // ---- chunk bitmaps ---------------------------------------------------------
+  const int trk_tok = tok_w0 + lane;
+  const bool trk_ok = lane < tokw && trk_tok < a.n_q;
+  const int64_t trk_base = ((int64_t)b * a.h_kv + r) * a.n_q + (trk_ok ? trk_tok : 0);
+  const uint32_t* trk_mask = a.mask + trk_base * a.words;
+  const float* trk_bias = a.bias + trk_base * a.t_all;
+  int trk_rank = 0, trk_wi = -1;
+  uint32_t trk_word = 0;
+  bool trk_has = false;
+
+  for (int i = tid; i < 5 * 64; i += 256) wgmask[i] = 0u;
+  __syncthreads();
+  if (wave_ok)
+    for (int wi = lane; wi < a.words; wi += 64) {
+      uint32_t m = 0u;
+      for (int t = 0; t < tokw; t++)
+        if (tok_w0 + t < a.n_q)
+          m |= a.mask[(((int64_t)b * a.h_kv + r) * a.n_q + tok_w0 + t) * a.words + wi];
+      wvmask[wave * 64 + wi] = m;
+      if (m) atomicOr(&wgmask[wi], m);
+    }
+  __syncthreads();
+  // tell the key-owner kernel which chunks this row tile attends
+  for (int wi = tid; wi < a.words; wi += 256) {
+    uint32_t m = wgmask[wi];
+    while (m) {
+      const int c = wi * 32 + __builtin_ctz(m);
+      m &= m - 1u;
+      if (c < a.t_all)
+        atomicOr(&a.colmask[((int64_t)hbi * a.t_all + c) * a.cwords + (tile >> 5)], 1u << (tile & 31));
+    }
+  }
+
+  // ---- tile iterator ---------------------------------------------------------
+  int it_wi = -1, it_sub = nsub - 1, it_u = -1;
+  uint32_t it_bits = 0u;
+  auto advance = [&]() -> bool {
+    if (it_u >= 0 && it_sub + 1 < nsub) { it_sub++; return true; }
+    while (it_bits == 0u) {
+      if (++it_wi >= a.words) return false;
+      it_bits = __builtin_amdgcn_readfirstlane(wgmask[it_wi]);
+    }
+    it_u = it_wi * 32 + __builtin_ctz(it_bits);
+    it_bits &= it_bits - 1u;
+    it_sub = 0;
+    return true;
+  };
+
+  // ---- tile copies -------------------------------------------------------------
+  const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
+  const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
+  const uint32_t lds0 = lds_addr_of(lds);
+  const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
+  const uint32_t ka_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ swz_a<D>(c_row)) << 4));
+  const uint32_t kt_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ swz_t<D>(c_row)) << 4));
+  const uint32_t va_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ swz_a<D>(c_row)) << 4));
+  const uint32_t k_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.ks_t * 2);
+  const uint32_t v_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.vs_t * 2);
+
+  // ---- operand read offsets ------------------------------------------------------
+  uint32_t a_rd[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++)
+    a_rd[ks] = (uint32_t)(n * C::ROW_BYTES + (((2 * ks + h) ^ swz_a<D>(n)) << 4));
+  const int s16 = lane & 15, a16 = (lane >> 4) & 1;
+  uint32_t t_rd[C::NDT];
+#pragma unroll
+  for (int t = 0; t < C::NDT; t++)
+    t_rd[t] = (uint32_t)((4 * h + (s16 >> 2)) * C::ROW_BYTES +
+                         ((((4 * t) ^ swz_t<D>(s16 >> 2)) + 2 * a16 + ((s16 & 3) >> 1)) << 4) + ((s16 & 1) << 3));
+
+  // first pass: running max, sum of exponentials and sum of exponentials times dP;
+  // D = <P, dP> = <dO, o> is taken from the latter two in fp32 (the stored bf16
+  // output would put its rounding error into every dz of the row)
+  float m_run = -INFINITY, l_run = 0.f, dn_run = 0.f, lse2 = 0.f, dsum = 0.f;
+  f32x16 dqacc[C::NDT];
+#pragma unroll
+  for (int t = 0; t < C::NDT; t++) dqacc[t] = zero16();
+  float db_acc = 0.f;
+
+  for (int pass = 0; pass < 2; pass++) {
+    const bool grad = pass == 1;
+    it_wi = -1; it_sub = nsub - 1; it_u = -1; it_bits = 0u;
+    trk_rank = 0; trk_wi = -1; trk_word = 0; trk_has = false;
+    float trk_next = (trk_ok && a.t_all > 0) ? trk_bias[0] : 0.f;
+    float bias_row = 0.f;
+    bool wave_on = false, diag = false;
+    while (advance()) {
+      const int cu = it_u, csub = it_sub;
+      const uint32_t soff_k = (uint32_t)(cu * a.block + csub * 64) * (uint32_t)a.ks_t * 2u;
+      const uint32_t soff_v = (uint32_t)(cu * a.block + csub * 64) * (uint32_t)a.vs_t * 2u;
+      __syncthreads();                      // the previous tile is no longer read
+#pragma unroll
+      for (int c = 0; c < C::COPIES; c++) {
+        copy16_to_lds(k_rs, lds0 + wave * 1024 + c * 4096, ka_off, soff_k + c * k_step);
+        copy16_to_lds(v_rs, lds0 + 2 * C::TILE_BYTES + wave * 1024 + c * 4096, va_off, soff_v + c * v_step);
+        if (grad)
+          copy16_to_lds(k_rs, lds0 + C::TILE_BYTES + wave * 1024 + c * 4096, kt_off, soff_k + c * k_step);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+
+      if (csub == 0) {
+        wave_on = wave_ok && ((__builtin_amdgcn_readfirstlane(wvmask[wave * 64 + (cu >> 5)]) >> (cu & 31)) & 1u);
+        diag = a.causal && cu == cw;
+        if (wave_on) {
+          float bt = 0.f;
+          trk_has = false;
+          if (!diag) {
+            bt = -INFINITY;
+            if (trk_ok) {
+              if ((cu >> 5) != trk_wi) { trk_wi = cu >> 5; trk_word = trk_mask[trk_wi]; }
+              if ((trk_word >> (cu & 31)) & 1u) {
+                trk_has = true;
+                bt = trk_next * kLog2e;
+                if (grad) a.biasd[trk_base * a.t_all + cu] = trk_next;
+                trk_rank++;
+                if (trk_rank < a.t_all) trk_next = trk_bias[trk_rank];
+              }
+            }
+          }
+          bias_row = __shfl(bt, n / a.g_q);
+        }
+      }
+      if (!wave_on) continue;
+      const int kpos0 = cu * a.block + csub * 64;
+
+      // S^T = K Q^T
+      f32x16 s[2] = {zero16(), zero16()};
+#pragma unroll
+      for (int i = 0; i < C::NS; i++)
+        s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(ka_t, a_rd, i), qf[i >> 1], s[i & 1], 0, 0, 0);
+      // key mask: causal inside the diagonal chunk, and the end of the sequence
+      {
+        const int k0 = kpos0 + 4 * h;
+        const int lim = min(diag ? row_pos - k0 : 0x7fffffff, a.n_kv - 1 - k0);
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+          for (int j = 0; j < 16; j++) {
+            const int c = kt * 32 + (j >> 2) * 8 + (j & 3);
+            s[kt][j] = c > lim ? -INFINITY : s[kt][j];
+          }
+      }
+      // dP^T = V dO^T
+      f32x16 dp[2] = {zero16(), zero16()};
+#pragma unroll
+      for (int i = 0; i < C::NS; i++)
+        dp[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(va_t, a_rd, i), dof[i >> 1], dp[i & 1], 0, 0, 0);
+      if (!grad) {
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+          for (int j = 0; j < 16; j++) mloc = fmaxf(mloc, s[kt][j]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float tmax = fmaf(mloc, a.c1, bias_row);
+        const float m_new = fmaxf(m_run, tmax);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        float lsum = 0.f, dnsum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+          for (int j = 0; j < 16; j++) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, bias_row - m_use));
+            lsum += e;
+            dnsum = fmaf(e, dp[kt][j], dnsum);
+          }
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+        l_run = l_run * corr + lsum;
+        dn_run = dn_run * corr + dnsum;
+        m_run = m_new;
+        continue;
+      }
+      // dS^T = P^T (dP^T - D), packed as the B operand of the second product
+      const float off = bias_row - lse2;
+      u32x4 pb[4];
+      float dssum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 16; k++) {
+        const int g = k >> 2, kt = g >> 1, j = 8 * (g & 1) + 2 * (k & 3);
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, off));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][j + 1], a.c1, off));
+        const float d0 = p0 * (dp[kt][j] - dsum);
+        const float d1 = p1 * (dp[kt][j + 1] - dsum);
+        dssum += d0 + d1;
+        pb[g][k & 3] = pack_bf16x2(d0, d1);
+      }
+      db_acc += dssum;
+      // dQ^T += K^T dS^T
+#pragma unroll
+      for (int i = 0; i < C::NS; i++) {
+        const int g = i / C::NDT, t = i % C::NDT;
+        dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(kt_t, t_rd, g, t),
+                                                           __builtin_bit_cast(bf16x8, pb[g]), dqacc[t], 0, 0, 0);
+      }
+      if (csub == nsub - 1) {
+        // bias gradient of chunk cu: sum over the keys (both lane halves) and the
+        // token's heads (adjacent lanes), written by the lane that tracks the token
+        float tot = db_acc + __shfl_xor(db_acc, 32);
+        for (int o = 1; o < a.g_q; o <<= 1) tot += __shfl_xor(tot, o);
+        const float mine = __shfl(tot, (lane * a.g_q) & 31);
+        if (!diag && trk_ok && trk_has) a.dbd[trk_base * a.t_all + cu] = mine;
+        db_acc = 0.f;
+      }
+    }
+    if (!grad) {
+      const float l_tot = l_run + __shfl_xor(l_run, 32);
+      const float dn_tot = dn_run + __shfl_xor(dn_run, 32);
+      lse2 = (m_run == -INFINITY ? 0.f : m_run) + __builtin_amdgcn_logf(l_tot);   // v_log_f32: log2
+      dsum = l_tot > 0.f ? dn_tot / l_tot : 0.f;
+    }
+  }
+
+  // ---- outputs -----------------------------------------------------------------
+  if (row_ok) {
+    const int64_t row = ((int64_t)b * a.h_q + my_head) * a.n_q + my_tok;
+    if (h == 0) { a.lse[row] = lse2; a.dsum[row] = dsum; }
+    float* dq = a.dq32 + row * D;
+#pragma unroll
+    for (int t = 0; t < C::NDT; t++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const int m0 = q4 * 8 + h * 4;
+        float4 w;
+        w.x = dqacc[t][q4 * 4 + 0] * a.scale; w.y = dqacc[t][q4 * 4 + 1] * a.scale;
+        w.z = dqacc[t][q4 * 4 + 2] * a.scale; w.w = dqacc[t][q4 * 4 + 3] * a.scale;
+        *reinterpret_cast<float4*>(dq + t * 32 + m0) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Routing backward: one wave per (batch, kv-head, token).
+// ---------------------------------------------------------------------------
+// u^p and p u^(p-1) for u > 0
+__device__ __forceinline__ void pow_and_slope(float u, float p, float& w, float& g) {
+  if (p == 2.f) { w = u * u; g = 2.f * u; }
+  else if (p == 1.f) { w = u; g = 1.f; }
+  else { w = __builtin_amdgcn_exp2f(p * __builtin_amdgcn_logf(u)); g = p * w / u; }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
+  constexpr int SEG = 64;
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  float* qs = reinterpret_cast<float*>(lds);                 // [G][D]
+  int* cidx = reinterpret_cast<int*>(qs + G * D);            // [t_c]
+  float* dwl = reinterpret_cast<float*>(cidx + a.t_c);       // [t_c]
+  float* dxs = dwl + a.t_c;                                  // [G][SEG]
+
+  const int lane = threadIdx.x;
+  const int tok = blockIdx.x % a.n_q;
+  const int hbi = blockIdx.x / a.n_q;
+  const int r = hbi % a.h_kv, b = hbi / a.h_kv;
+  const int n_cand = a.causal ? max(tok / a.block - a.window, 0) : a.t_c;
+  const int64_t trow = ((int64_t)b * a.h_kv + r) * a.n_q + tok;
+  const uint32_t* mrow = a.mask + trow * a.words;
+  const float* dbrow = a.dbd + trow * a.t_all;
+  const float* kb = a.kbar + ((int64_t)b * a.h_kv + r) * a.t_c * D;
+
+  for (int i = lane; i < G * D; i += 64) {
+    const int hh = i / D, d = i % D;
+    qs[i] = bf16_bits_to_f32(a.q[b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t + d]);
+  }
+  // routed candidates, ascending
+  int n_r = 0;
+  for (int base = 0; base < n_cand; base += 64) {
+    const int c = base + lane;
+    const bool bit = c < n_cand && ((mrow[c >> 5] >> (c & 31)) & 1u);
+    const uint64_t bal = __ballot(bit);
+    if (bit) cidx[n_r + __popcll(bal & ((1ull << lane) - 1ull))] = c;
+    n_r += __popcll(bal);
+  }
+  __syncthreads();
+
+  float acc_q[G][2];            // routing part of dq: this lane's d pair (D = 128) or single d (D = 64)
+#pragma unroll
+  for (int hh = 0; hh < G; hh++) acc_q[hh][0] = acc_q[hh][1] = 0.f;
+
+  if (n_r > 0) {
+    float tauh[G];
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) tauh[hh] = a.tau[((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok];
+    float dsum = 0.f;
+    for (int e = lane; e < n_r; e += 64) dsum += dbrow[cidx[e]];
+    const float dmean = wave_sum(dsum) / (float)n_r;
+
+    // sweep A: scores, weights, slopes; S0 = sum g, S1 = sum g dw_hat per head
+    float s0[G], s1[G];
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) s0[hh] = s1[hh] = 0.f;
+    for (int e = lane; e < n_r; e += 64) {
+      const int c = cidx[e];
+      const float4* krow = reinterpret_cast<const float4*>(kb + (int64_t)c * D);
+      float x[G];
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) x[hh] = 0.f;
+#pragma unroll 2
+      for (int d4 = 0; d4 < D / 4; d4++) {
+        const float4 kv = krow[d4];
+#pragma unroll
+        for (int hh = 0; hh < G; hh++) {
+          const float4 qv = *reinterpret_cast<const float4*>(qs + hh * D + d4 * 4);
+          x[hh] = fmaf(qv.x, kv.x, fmaf(qv.y, kv.y, fmaf(qv.z, kv.z, fmaf(qv.w, kv.w, x[hh]))));
+        }
+      }
+      float gd[G], wsum = 0.f;
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        const float u = x[hh] * a.xscale - tauh[hh];
+        float wv = 0.f;
+        gd[hh] = 0.f;
+        if (u > 0.f) pow_and_slope(u, a.pexp, wv, gd[hh]);
+        wsum += wv;
+      }
+      // dw_hat = dlnw / w / g_q with w = wsum / g_q
+      const float dwh = wsum > 0.f ? (dbrow[c] - dmean) / (a.sigma * wsum) : 0.f;
+      dwl[e] = dwh;
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        s0[hh] += gd[hh];
+        s1[hh] += gd[hh] * dwh;
+        a.dxd[(((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c] = gd[hh];
+      }
+    }
+    float ratio[G];
+#pragma unroll
+    for (int hh = 0; hh < G; hh++) {
+      const float t0 = wave_sum(s0[hh]), t1 = wave_sum(s1[hh]);
+      ratio[hh] = t0 > 0.f ? t1 / t0 : 0.f;
+    }
+    // sweep B, one segment of SEG routed chunks at a time: dx, then dq += dx kbar
+    for (int e0 = 0; e0 < n_r; e0 += SEG) {
+      const int e = e0 + lane;
+      __syncthreads();
+      if (e < n_r) {
+        const int c = cidx[e];
+        const float dwh = dwl[e];
+#pragma unroll
+        for (int hh = 0; hh < G; hh++) {
+          float* px = a.dxd + (((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c;
+          const float dx = *px * (dwh - ratio[hh]);
+          *px = dx;
+          dxs[hh * SEG + lane] = dx;
+        }
+      }
+      __syncthreads();
+      const int cnt = min(SEG, n_r - e0);
+      for (int j = 0; j < cnt; j++) {
+        const int c = cidx[e0 + j];
+        float k0, k1 = 0.f;
+        if (D == 128) {
+          const float2 kv = *reinterpret_cast<const float2*>(kb + (int64_t)c * D + 2 * lane);
+          k0 = kv.x; k1 = kv.y;
+        } else {
+          k0 = kb[(int64_t)c * D + lane];
+        }
+#pragma unroll
+        for (int hh = 0; hh < G; hh++) {
+          const float dx = dxs[hh * SEG + j];
+          acc_q[hh][0] = fmaf(dx, k0, acc_q[hh][0]);
+          acc_q[hh][1] = fmaf(dx, k1, acc_q[hh][1]);
+        }
+      }
+    }
+  }
+  // final dq = attention part + routing part
+#pragma unroll
+  for (int hh = 0; hh < G; hh++) {
+    const int64_t row = ((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok;
+    uint16_t* out = a.dq + b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t;
+    if (D == 128) {
+      const float2 base = *reinterpret_cast<const float2*>(a.dq32 + row * D + 2 * lane);
+      *reinterpret_cast<uint32_t*>(out + 2 * lane) =
+          pack_bf16x2(fmaf(a.xscale, acc_q[hh][0], base.x), fmaf(a.xscale, acc_q[hh][1], base.y));
+    } else {
+      out[lane] = (uint16_t)f32_to_bf16_bits(fmaf(a.xscale, acc_q[hh][0], a.dq32[row * D + lane]));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Key-owner kernel: one 64-key tile per workgroup.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
+  using C = BCfg<D>;
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* qa_t = lds;                            // Q rows, A-operand layout
+  char* qt_t = lds + C::TILE_BYTES;            // Q rows, transposing-read layout
+  char* da_t = lds + 2 * C::TILE_BYTES;        // dO rows, A-operand layout
+  char* dt_t = lds + 3 * C::TILE_BYTES;        // dO rows, transposing-read layout
+  float* lse_s = reinterpret_cast<float*>(lds + 4 * C::TILE_BYTES);   // [64] per-row scalars
+  float* dsum_s = lse_s + 64;
+  float* bias_s = dsum_s + 64;
+  float* dx_s = bias_s + 64;
+  int* pos_s = reinterpret_cast<int*>(dx_s + 64);
+  float* red = reinterpret_cast<float*>(pos_s + 64);                  // [4][D] dkbar partials
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 31, h = lane >> 5;
+  const int kh = wave & 1, rh = wave >> 1;
+  const int hbi = blockIdx.x % a.hb;
+  const int ktile = blockIdx.x / a.hb;          // early key tiles (the most rows) first
+  const int r = hbi % a.h_kv, b = hbi / a.h_kv;
+  const int kpos0 = ktile * 64;
+  const int c = kpos0 / a.block;
+  const int tok_step = 64 / a.g_q;              // tokens per 64-row step
+
+  // K and V fragments of this wave's 32 keys (B operands)
+  bf16x8 kf[D / 16], vf[D / 16];
+  const int my_key = kpos0 + kh * 32 + n;
+  {
+    const bool ok = my_key < a.n_kv;
+    const uint16_t* kp = a.k + b * a.ks_b + r * a.ks_h + (int64_t)(ok ? my_key : 0) * a.ks_t + h * 8;
+    const uint16_t* vp = a.v + b * a.vs_b + r * a.vs_h + (int64_t)(ok ? my_key : 0) * a.vs_t + h * 8;
+    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) {
+      kf[ks] = ok ? *reinterpret_cast<const bf16x8*>(kp + ks * 16) : z;
+      vf[ks] = ok ? *reinterpret_cast<const bf16x8*>(vp + ks * 16) : z;
+    }
+  }
+
+  const u32x4 q_rs = make_rsrc(a.q + b * a.qs_b + (int64_t)r * a.g_q * a.qs_h,
+                               ((int64_t)(a.g_q - 1) * a.qs_h + ((int64_t)a.n_q - 1) * a.qs_t + D) * 2);
+  const u32x4 o_rs = make_rsrc(a.d_o + b * a.os_b + (int64_t)r * a.g_q * a.os_h,
+                               ((int64_t)(a.g_q - 1) * a.os_h + ((int64_t)a.n_q - 1) * a.os_t + D) * 2);
+  const uint32_t lds0 = lds_addr_of(lds);
+  const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
+  const int c_tok = c_row / a.g_q, c_head = c_row % a.g_q;
+  const uint32_t q_base = (uint32_t)((c_tok * (int)a.qs_t + c_head * (int)a.qs_h) * 2);
+  const uint32_t o_base = (uint32_t)((c_tok * (int)a.os_t + c_head * (int)a.os_h) * 2);
+  const uint32_t qa_off = q_base + ((c_pos ^ swz_a<D>(c_row)) << 4);
+  const uint32_t qt_off = q_base + ((c_pos ^ swz_t<D>(c_row)) << 4);
+  const uint32_t da_off = o_base + ((c_pos ^ swz_a<D>(c_row)) << 4);
+  const uint32_t dt_off = o_base + ((c_pos ^ swz_t<D>(c_row)) << 4);
+  const uint32_t q_step = (uint32_t)((C::ROWS_PER_COPY / a.g_q) * (int)a.qs_t * 2);
+  const uint32_t o_step = (uint32_t)((C::ROWS_PER_COPY / a.g_q) * (int)a.os_t * 2);
+
+  uint32_t a_rd[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++)
+    a_rd[ks] = (uint32_t)((rh * 32 + n) * C::ROW_BYTES + (((2 * ks + h) ^ swz_a<D>(n)) << 4));
+  const int s16 = lane & 15, a16 = (lane >> 4) & 1;
+  uint32_t t_rd[C::NDT];
+#pragma unroll
+  for (int t = 0; t < C::NDT; t++)
+    t_rd[t] = (uint32_t)((rh * 32 + 4 * h + (s16 >> 2)) * C::ROW_BYTES +
+                         ((((4 * t) ^ swz_t<D>(s16 >> 2)) + 2 * a16 + ((s16 & 3) >> 1)) << 4) + ((s16 & 1) << 3));
+
+  f32x16 dkacc[C::NDT], dvacc[C::NDT];
+#pragma unroll
+  for (int t = 0; t < C::NDT; t++) { dkacc[t] = zero16(); dvacc[t] = zero16(); }
+  float kb0 = 0.f, kb1 = 0.f;      // dkbar partial of this thread's d pair over its 16 rows per step
+
+  const uint32_t* cm = a.colmask + ((int64_t)hbi * a.t_all + c) * a.cwords;
+  for (int wi = 0; wi < a.cwords; wi++) {
+    uint32_t bits = __builtin_amdgcn_readfirstlane(cm[wi]);
+    while (bits) {
+      const int T = wi * 32 + __builtin_ctz(bits);
+      bits &= bits - 1u;
+      for (int half = 0; half < 2; half++) {
+        const int tok0 = T * 2 * tok_step + half * tok_step;
+        if (tok0 >= a.n_q) continue;
+        __syncthreads();                    // the previous step is no longer read
+        int have = 0;
+        if (tid < 64) {
+          const int tk = tok0 + tid / a.g_q, head = r * a.g_q + tid % a.g_q;
+          const bool ok = tk < a.n_q;
+          const int tkc = ok ? tk : a.n_q - 1;
+          const int64_t trow = ((int64_t)b * a.h_kv + r) * a.n_q + tkc;
+          const int64_t hrow = ((int64_t)b * a.h_q + head) * a.n_q + tkc;
+          const bool bit = ok && ((a.mask[trow * a.words + (c >> 5)] >> (c & 31)) & 1u);
+          const int cdiag = tkc / a.block;
+          const bool isdiag = a.causal && c == cdiag;
+          const int n_cand = a.causal ? max(cdiag - a.window, 0) : a.t_c;
+          float bv = -INFINITY, dx = 0.f;
+          if (bit) {
+            bv = isdiag ? 0.f : a.biasd[trow * a.t_all + c] * kLog2e;
+            if (c < n_cand) dx = a.dxd[hrow * a.t_all + c];
+          }
+          bias_s[tid] = bv;
+          dx_s[tid] = dx;
+          lse_s[tid] = a.lse[hrow];
+          dsum_s[tid] = a.dsum[hrow];
+          pos_s[tid] = a.causal ? tkc : 0x7fffffff;
+          have = bit ? 1 : 0;
+        }
+        if (!__syncthreads_or(have)) continue;
+        const uint32_t soff_q = (uint32_t)tok0 * (uint32_t)a.qs_t * 2u;
+        const uint32_t soff_o = (uint32_t)tok0 * (uint32_t)a.os_t * 2u;
+#pragma unroll
+        for (int i = 0; i < C::COPIES; i++) {
+          const uint32_t la = lds0 + wave * 1024 + i * 4096;
+          copy16_to_lds(q_rs, la, qa_off, soff_q + i * q_step);
+          copy16_to_lds(q_rs, la + C::TILE_BYTES, qt_off, soff_q + i * q_step);
+          copy16_to_lds(o_rs, la + 2 * C::TILE_BYTES, da_off, soff_o + i * o_step);
+          copy16_to_lds(o_rs, la + 3 * C::TILE_BYTES, dt_off, soff_o + i * o_step);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+
+        // S = Q K^T and dP = dO V^T for this wave's 32 rows x 32 keys
+        f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(qa_t + a_rd[ks]), kf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(da_t + a_rd[ks]), vf[ks], dp, 0, 0, 0);
+        }
+        u32x4 pp[2], pd[2];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          const int row0 = rh * 32 + 8 * q4 + 4 * h;
+          const float4 l4 = *reinterpret_cast<const float4*>(lse_s + row0);
+          const float4 d4 = *reinterpret_cast<const float4*>(dsum_s + row0);
+          const float4 b4 = *reinterpret_cast<const float4*>(bias_s + row0);
+          const int4 p4 = *reinterpret_cast<const int4*>(pos_s + row0);
+          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+          const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
+          const int ps[4] = {p4.x, p4.y, p4.z, p4.w};
+          float pv[4], dv[4];
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            const int j = q4 * 4 + i;
+            const bool dead = my_key > ps[i] || my_key >= a.n_kv;
+            const float p = dead ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bs[i] - ls[i]));
+            pv[i] = p;
+            dv[i] = p * (dp[j] - ds[i]);
+          }
+          pp[q4 >> 1][(q4 & 1) * 2 + 0] = pack_bf16x2(pv[0], pv[1]);
+          pp[q4 >> 1][(q4 & 1) * 2 + 1] = pack_bf16x2(pv[2], pv[3]);
+          pd[q4 >> 1][(q4 & 1) * 2 + 0] = pack_bf16x2(dv[0], dv[1]);
+          pd[q4 >> 1][(q4 & 1) * 2 + 1] = pack_bf16x2(dv[2], dv[3]);
+        }
+        // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over this wave's 32 rows)
+#pragma unroll
+        for (int g = 0; g < 2; g++)
+#pragma unroll
+          for (int t = 0; t < C::NDT; t++) {
+            dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(dt_t, t_rd, g, t),
+                                                               __builtin_bit_cast(bf16x8, pp[g]), dvacc[t], 0, 0, 0);
+            dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(qt_t, t_rd, g, t),
+                                                               __builtin_bit_cast(bf16x8, pd[g]), dkacc[t], 0, 0, 0);
+          }
+        // dkbar += sum_rows dx q: thread (wave, lane) takes d = 2 lane, 2 lane + 1 and rows 16 wave ..
+        if (2 * lane < D) {
+#pragma unroll 4
+          for (int rr = 0; rr < 16; rr++) {
+            const int row = wave * 16 + rr;
+            const float dx = dx_s[row];
+            const uint32_t w = *reinterpret_cast<const uint32_t*>(
+                qa_t + row * C::ROW_BYTES + ((((2 * lane) >> 3) ^ swz_a<D>(row)) << 4) + ((2 * lane) & 7) * 2);
+            kb0 = fmaf(dx, bf16_lo(w), kb0);
+            kb1 = fmaf(dx, bf16_hi(w), kb1);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- combine the two row halves and write ------------------------------------
+  __syncthreads();
+  if (2 * lane < D) { red[wave * D + 2 * lane] = kb0; red[wave * D + 2 * lane + 1] = kb1; }
+  float* xch = reinterpret_cast<float*>(lds);          // [2 kh][2 tensors][NDT*16][64 lanes]
+  if (rh == 1) {
+#pragma unroll
+    for (int t = 0; t < C::NDT; t++)
+#pragma unroll
+      for (int j = 0; j < 16; j++) {
+        xch[((kh * 2 + 0) * C::NDT * 16 + t * 16 + j) * 64 + lane] = dkacc[t][j];
+        xch[((kh * 2 + 1) * C::NDT * 16 + t * 16 + j) * 64 + lane] = dvacc[t][j];
+      }
+  }
+  __syncthreads();
+  if (rh == 0 && my_key < a.n_kv) {
+    const float kscale = c < a.t_c ? a.xscale / (float)a.block : 0.f;
+    uint16_t* dkp = a.dk + b * a.ks_b + r * a.ks_h + (int64_t)my_key * a.ks_t;
+    uint16_t* dvp = a.dv + b * a.vs_b + r * a.vs_h + (int64_t)my_key * a.vs_t;
+#pragma unroll
+    for (int t = 0; t < C::NDT; t++)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const int d0 = t * 32 + q4 * 8 + h * 4;
+        float kv[4], vv[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int j = q4 * 4 + i;
+          const float kbar_g = red[d0 + i] + red[D + d0 + i] + red[2 * D + d0 + i] + red[3 * D + d0 + i];
+          kv[i] = (dkacc[t][j] + xch[((kh * 2 + 0) * C::NDT * 16 + t * 16 + j) * 64 + lane]) * a.scale +
+                  kbar_g * kscale;
+          vv[i] = dvacc[t][j] + xch[((kh * 2 + 1) * C::NDT * 16 + t * 16 + j) * 64 + lane];
+        }
+        uint2 w;
+        w.x = pack_bf16x2(kv[0], kv[1]); w.y = pack_bf16x2(kv[2], kv[3]);
+        *reinterpret_cast<uint2*>(dkp + d0) = w;
+        w.x = pack_bf16x2(vv[0], vv[1]); w.y = pack_bf16x2(vv[2], vv[3]);
+        *reinterpret_cast<uint2*>(dvp + d0) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+static size_t al256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t backward_workspace_bytes(const dash_params& p, const Layout& L) {
+  const size_t rows_q = (size_t)p.batch * p.h_q * p.n_q, rows_kv = (size_t)p.batch * p.h_kv * p.n_q;
+  const int tok_tile = 4 * (32 / L.g_q);
+  const int n_tiles = (p.n_q + tok_tile - 1) / tok_tile;
+  const int cwords = (n_tiles + 31) / 32;
+  return 2 * al256(rows_q * 4) + 2 * al256(rows_kv * L.t_all * 4) + al256(rows_q * L.t_all * 4) +
+         al256(rows_q * p.head_dim * 4) + al256((size_t)p.batch * p.h_kv * L.t_all * cwords * 4);
+}
+
+template <int D, int G> static hipError_t launch_route(const BwdArgs& a, int batch, hipStream_t st) {
+  const size_t lds = (size_t)G * D * 4 + (size_t)a.t_c * 8 + (size_t)G * 64 * 4 + 64;
+  auto kern = bwd_route_kernel<D, G>;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)batch * a.h_kv * a.n_q)), dim3(64), lds, st, a);
+  return hipGetLastError();
+}
+
+template <int D> static hipError_t launch_route_g(const BwdArgs& a, int batch, hipStream_t st) {
+  switch (a.g_q) {
+    case 1: return launch_route<D, 1>(a, batch, st);
+    case 2: return launch_route<D, 2>(a, batch, st);
+    case 4: return launch_route<D, 4>(a, batch, st);
+    case 8: return launch_route<D, 8>(a, batch, st);
+    default: return launch_route<D, 16>(a, batch, st);
+  }
+}
+
+template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hipStream_t st) {
+  using C = BCfg<D>;
+  hipError_t e;
+  {
+    const size_t nwords = (size_t)a.hb * a.t_all * a.cwords;
+    hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3((unsigned)((nwords + 255) / 256 < 1024 ? (nwords + 255) / 256 : 1024)),
+                       dim3(256), 0, st, a.colmask, nwords);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
+    const size_t lds = 3 * C::TILE_BYTES + 5 * 64 * 4;
+    auto kern = bwd_q_kernel<D>;
+    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+      return e;
+    hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if ((e = launch_route_g<D>(a, batch, st)) != hipSuccess) return e;
+  {
+    const size_t xch = (size_t)2 * 2 * C::NDT * 16 * 64 * 4;
+    const size_t tiles = 4 * C::TILE_BYTES;
+    const size_t lds = (xch > tiles ? xch : tiles) + 5 * 64 * 4 + 4 * D * 4;
+    auto kern = bwd_kv_kernel<D>;
+    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+      return e;
+    const int ktiles = (a.n_kv + 63) / 64;
+    hipLaunchKernelGGL(kern, dim3(ktiles * a.hb), dim3(256), lds, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_backward(const dash_params& p, const Layout& L, const void* q, const void* k, const void* v,
+                           const void* d_o, const float* kbar, const uint32_t* mask,
+                           const float* bias, const float* tau, void* dq, void* dk, void* dv, char* ws,
+                           hipStream_t st) {
+  BwdArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
+  a.d_o = (const uint16_t*)d_o;
+  a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
+  a.kbar = kbar; a.mask = mask; a.bias = bias; a.tau = tau;
+  a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv; a.block = p.block_size;
+  a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.causal = p.causal; a.window = p.window;
+  a.hb = p.h_kv * p.batch;
+  const int tok_tile = 4 * (32 / L.g_q);
+  a.n_tiles = (p.n_q + tok_tile - 1) / tok_tile;
+  a.cwords = (a.n_tiles + 31) / 32;
+  a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
+  a.ks_b = p.k_stride[0]; a.ks_h = p.k_stride[1]; a.ks_t = p.k_stride[2];
+  a.vs_b = p.v_stride[0]; a.vs_h = p.v_stride[1]; a.vs_t = p.v_stride[2];
+  a.os_b = p.o_stride[0]; a.os_h = p.o_stride[1]; a.os_t = p.o_stride[2];
+  a.c1 = L.scale * kLog2e; a.scale = L.scale; a.xscale = L.xscale; a.pexp = L.pexp; a.sigma = p.sigma;
+  const size_t rows_q = (size_t)p.batch * p.h_q * p.n_q, rows_kv = (size_t)p.batch * p.h_kv * p.n_q;
+  size_t off = 0;
+  a.lse = (float*)(ws + off);    off += al256(rows_q * 4);
+  a.dsum = (float*)(ws + off);   off += al256(rows_q * 4);
+  a.biasd = (float*)(ws + off);  off += al256(rows_kv * L.t_all * 4);
+  a.dbd = (float*)(ws + off);    off += al256(rows_kv * L.t_all * 4);
+  a.dxd = (float*)(ws + off);    off += al256(rows_q * L.t_all * 4);
+  a.dq32 = (float*)(ws + off);   off += al256(rows_q * p.head_dim * 4);
+  a.colmask = (uint32_t*)(ws + off);
+  return p.head_dim == 128 ? launch_bwd_t<128>(a, p.batch, st) : launch_bwd_t<64>(a, p.batch, st);
+}
+
+}  // namespace dash

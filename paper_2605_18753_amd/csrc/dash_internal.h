@@ -52,6 +52,13 @@ hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, 
 hipError_t launch_s2_f32(const dash_params& p, const Layout& L, const void* q, const void* k,
                          const void* v, void* o, const uint32_t* mask, const float* bias,
                          bool dense, hipStream_t st);
+// Backward of the bf16 prefill path (block-mean summaries): scratch size and the
+// kernel sequence; ws must hold backward_workspace_bytes() bytes.
+size_t backward_workspace_bytes(const dash_params& p, const Layout& L);
+hipError_t launch_backward(const dash_params& p, const Layout& L, const void* q, const void* k, const void* v,
+                           const void* d_o, const float* kbar, const uint32_t* mask,
+                           const float* bias, const float* tau, void* dq, void* dk, void* dv, char* ws,
+                           hipStream_t st);
 hipError_t launch_decode_s2(const dash_params& p, const Layout& L, const void* q, const void* k,
                             const void* v, void* o, const uint32_t* mask, const float* bias,
                             float* partials, bool dense, hipStream_t st);

@@ -1,0 +1,108 @@
+"""GPU parity of the backward pass (dash_attn_backward through the C ABI) against
+the fp64 backward oracle, element by element, on inputs small enough for the
+oracle to process every row."""
+import numpy as np
+import pytest
+import torch
+
+import parity_util as U
+from oracle import dash_oracle as orc
+from oracle import dash_oracle_bwd as bwd
+from paper_2605_18753_amd import binding as B
+from paper_2605_18753_amd.inputs import Workload, make_inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def gen(w):
+    return tuple(t.to(DEV) for t in make_inputs(w, "cpu"))
+
+
+def run_backward(w, q, k, v, run, d_o):
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    # poison the outputs: every element must be written
+    for t in (dq, dk, dv):
+        t.fill_(float("nan"))
+    ws = B.alloc_backward_workspace(run.params, DEV)
+    B.dash_attn_backward(run.params, q, k, v, d_o, run.kbar, run.lists, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    return dq, dk, dv
+
+
+def rowwise_check(name, got, ref, allow, tol=2e-2):
+    """Row by row (last axis = head_dim): |got - ref| <= tol * scale_row + allow,
+    scale_row = the row's largest reference magnitude, floored at a tenth of
+    the median over rows so that near-zero rows are not held to a relative bar."""
+    rowmax = np.abs(ref).max(axis=-1, keepdims=True)
+    floor = 0.1 * np.median(rowmax)
+    bound = tol * np.maximum(rowmax, floor) + allow
+    err = np.abs(got - ref)
+    bad = err > bound
+    assert not bad.any(), (f"{name}: {int(bad.sum())} elements off, worst excess "
+                           f"{(err - bound).max():.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}, "
+                           f"ref there {ref[np.unravel_index(np.argmax(err - bound), err.shape)]:.3e}")
+    return float((err / np.maximum(rowmax, floor)).max())
+
+
+CASES = [
+    # name, batch, h_q, h_kv, n, d, block, extra
+    ("gqa2", 1, 4, 2, 512, 128, 64, {}),
+    ("mha_needles", 2, 2, 2, 448, 128, 64, {"needles": 2, "offset_sigma": 0.0}),
+    ("gqa4_ragged", 1, 4, 1, 600, 128, 64, {"offset_sigma": 0.8}),
+    ("gqa8_b128_d64", 1, 8, 1, 768, 64, 128, {"offset_sigma": 0.8}),
+    ("gqa16", 1, 16, 1, 384, 128, 64, {"offset_sigma": 0.8}),
+    ("alpha2_gamma", 1, 4, 2, 512, 128, 64, {"alpha": 2.0, "gamma": 1.5}),
+    ("alpha125_sigma", 1, 4, 2, 512, 128, 64, {"alpha": 1.25, "sigma": 2.0, "offset_sigma": 1.0}),
+    ("window1", 1, 4, 2, 512, 128, 64, {"window": 1, "offset_sigma": 0.8}),
+    ("noncausal", 1, 4, 2, 512, 128, 64, {"causal": False, "offset_sigma": 0.8}),
+    ("one_chunk", 1, 4, 2, 50, 128, 64, {}),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_backward_matches_the_oracle(case):
+    name, batch, h_q, h_kv, n, d, block, extra = case
+    w = Workload(name, batch, h_q, h_kv, n, n, d, block, seed=17, **extra)
+    q, k, v = gen(w)
+    gen_do = torch.Generator().manual_seed(99)
+    d_o = torch.randn(q.shape, generator=gen_do).to(torch.bfloat16).to(DEV)
+    run = U.run_prefill(w, q, k, v)
+    dq, dk, dv = run_backward(w, q, k, v, run, d_o)
+    for t in (dq, dk, dv):
+        assert torch.isfinite(t.float()).all(), "an output element was not written or is not finite"
+
+    prm = U.oracle_params(w)
+    g = w.g_q
+    qn, kn, vn, don = U.to_np(q).astype(np.float64), U.to_np(k).astype(np.float64), \
+        U.to_np(v).astype(np.float64), U.to_np(d_o).astype(np.float64)
+    t_all = B.list_stride(run.params)
+    worst = {}
+    for b in range(batch):
+        for r in range(h_kv):
+            # the comparison presumes the same support on both sides
+            kbar = orc.block_mean_summaries(kn[b, r], block)
+            mism = 0
+            for i in range(n):
+                rr = orc.dash_row_at(qn[b, r * g:(r + 1) * g, i], kn[b, r], vn[b, r], kbar, prm, i)
+                bits = U.mask_bits(run.lists.mask[b, r, i].cpu().numpy(), t_all)
+                got = set(np.nonzero(bits[:rr.n_cand])[0].tolist())
+                mism += got != set(rr.routed.tolist())
+            assert mism == 0, f"{mism} rows route differently on the two sides: choose another seed"
+            sl = slice(r * g, (r + 1) * g)
+            ref = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm)
+            hi = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, margin_shift=1e-6)
+            lo = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, margin_shift=-1e-6)
+            for nm, got, j in (("dq", U.to_np(dq[b, sl]), 0), ("dk", U.to_np(dk[b, r]), 1),
+                               ("dv", U.to_np(dv[b, r]), 2)):
+                allow = 3.0 * (np.abs(hi[j] - ref[j]) + np.abs(lo[j] - ref[j]))
+                e = rowwise_check(f"{name} {nm}[{b},{r}]", got.astype(np.float64), ref[j], allow)
+                worst[nm] = max(worst.get(nm, 0.0), e)
+            if n >= 2 * block:
+                # the path through the routing scores into the block means must be a visible part
+                # of dk, or the comparison above would not notice its absence
+                direct = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, kbar=kbar)[1]
+                rowmax = np.abs(ref[1]).max(axis=-1)
+                share = np.abs(ref[1] - direct).max(axis=-1) / np.maximum(rowmax, 0.1 * np.median(rowmax))
+                assert share.max() > 0.05, share.max()
+    print(f"{name}: worst row-relative error dq {worst['dq']:.2e} dk {worst['dk']:.2e} dv {worst['dv']:.2e}")

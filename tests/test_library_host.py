@@ -123,6 +123,32 @@ def test_ragged_decode_argument_errors():
                                        256, 1 << 40, None) == -1                          # one query per sequence
 
 
+def test_backward_argument_errors():
+    lib = B.load_library()
+    p = params()
+    need = B.backward_workspace_bytes(p)
+    assert need > 2 * 8 * 1024 * 4 + 8 * 1024 * 128 * 4
+    ptrs = [256] * 11
+    for i in range(11):
+        bad = list(ptrs)
+        bad[i] = None
+        assert lib.dash_attn_backward(ctypes.byref(p), *bad, 256, need, None) == -1, i
+    assert lib.dash_attn_backward(ctypes.byref(p), *ptrs, None, need, None) == -3
+    assert lib.dash_attn_backward(ctypes.byref(p), *ptrs, 256, need - 1, None) == -3
+    assert lib.dash_attn_backward(ctypes.byref(p), *ptrs, 257, need, None) == -3
+    n = ctypes.c_size_t(0)
+    for kw in (dict(dtype=0), dict(n_q=512, n_kv=1024)):            # fp32 tensors; a chunked prefill
+        pu = params(**kw)
+        assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(pu), ctypes.byref(n)) == -2
+        assert lib.dash_attn_backward(ctypes.byref(pu), *ptrs, 256, 1 << 40, None) == -2
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(p), None) == -1
+    big = params(h_q=16, h_kv=1, n_q=131072, n_kv=131072)          # a 16-head slice of q spans 512 MiB: fine
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(big), ctypes.byref(n)) == 0
+    far = params()
+    far.q_stride[1] = 1 << 31                                       # heads 4 GiB apart: 32-bit offsets do not reach
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(far), ctypes.byref(n)) == -2
+
+
 def test_strerror():
     lib = B.load_library()
     assert lib.dash_strerror(0) == b"ok"
