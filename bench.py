@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--small", action="store_true", help="shrunken shapes (debugging)")
     ap.add_argument("--paper-protocol", action="store_true",
@@ -130,6 +131,30 @@ def bench_prefill(w, steps, warmup, torch, B, make_inputs):
     t_dense = timed(lambda: B.dense_attn(p, q, k, v, od, ws), steps, warmup, torch)
     res = dict(ms_step=t_all, ms_stage0=t_s0, ms_stage0_learned=t_s0l, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
     del q, k, v, o, od, ws, lists, kbar, kbar_l
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_backward(w, steps, warmup, torch, B, make_inputs):
+    """Forward and backward of the training-shaped workload (the backward reuses the
+    forward's mask, bias and thresholds)."""
+    dev = "cuda:0"
+    q, k, v = make_inputs(w, dev)
+    o = torch.empty_like(q)
+    d_o = torch.randn(q.shape, device=dev, dtype=torch.float32).to(q.dtype)
+    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
+    lists = B.Lists.allocate(p, dev, idx=False)
+    ws = B.alloc_workspace(p, dev)
+    wsb = B.alloc_backward_workspace(p, dev)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws)
+    torch.cuda.synchronize()
+    st = prefill_stats(w, lists, torch)
+    t_f = timed(lambda: B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws), steps, warmup, torch)
+    t_b = timed(lambda: B.dash_attn_backward(p, q, k, v, d_o, kbar, lists, dq, dk, dv, wsb), steps, warmup, torch)
+    res = dict(ms_forward=t_f, ms_backward=t_b, **st)
+    del q, k, v, o, d_o, dq, dk, dv, ws, wsb, lists, kbar
     torch.cuda.empty_cache()
     return res
 
@@ -299,7 +324,7 @@ def main():
         sys.exit(2)
     import torch
     from paper_2605_18753_amd import binding as B
-    from paper_2605_18753_amd.inputs import C2, C3, make_inputs
+    from paper_2605_18753_amd.inputs import C2, C3, C5, make_inputs
     B.load_library()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = C2
@@ -330,6 +355,8 @@ def main():
     if not a.no_decode:
         dec = dict(gamma1=bench_decode(wd, max(a.steps, 20), a.warmup, torch, B, make_inputs),
                    gamma04=bench_decode(wd.replace(gamma=0.4), max(a.steps, 20), a.warmup, torch, B, make_inputs))
+    wb = C5.replace(n_q=2048, n_kv=2048, batch=1, name="C5_small") if a.small else C5
+    bwd = None if a.no_backward else bench_backward(wb, a.steps, a.warmup, torch, B, make_inputs)
     cpu = None if a.no_cpu else cpu_baseline(w, a.cpu_seconds, torch, make_inputs)
     gemm = None if a.small else gemm_context(torch)
 
@@ -376,6 +403,15 @@ def main():
                 "stage2_exec_mfma_frac": tf(res75["f_exec"], res75["ms_stage2"]) / MFMA_BF16_PEAK_TFLOPS,
                 "stage2_alg_mfma_frac": tf(res75["f_alg"], res75["ms_stage2"]) / MFMA_BF16_PEAK_TFLOPS,
                 "f_alg_over_f_exec": res75["f_alg"] / res75["f_exec"],
+            },
+            # backward of the training-shaped workload: 5 matrix products per attended (query, key)
+            # pair against the forward's 2, so its flops are 2.5 x the forward's f_alg
+            "backward": None if bwd is None else {
+                "workload": wb.name, "ms_forward": bwd["ms_forward"], "ms_backward": bwd["ms_backward"],
+                "backward_over_forward": bwd["ms_backward"] / bwd["ms_forward"],
+                "chunk_sparsity": bwd["sparsity"],
+                "backward_alg_tflops": tf(2.5 * bwd["f_alg"], bwd["ms_backward"]),
+                "backward_alg_mfma_frac": tf(2.5 * bwd["f_alg"], bwd["ms_backward"]) / MFMA_BF16_PEAK_TFLOPS,
             },
             "decode": None if dec is None else {
                 "workload": wd.name,
