@@ -63,23 +63,29 @@ template <int D> struct BCfg {
   static constexpr int NS = D / 8;
 };
 
-// chunk permutations of a 64-row tile: `a` for rows read as an MFMA A operand,
-// `t` for rows read through the transposing read (same choices as the forward)
-template <int D> __device__ __forceinline__ int swz_a(int row) {
-  return D == 128 ? (row & 15) : ((row >> 1) & 7);
+// Chunk permutation of a 64-row tile (position of logical 16-byte chunk c of row
+// `row` is c ^ swz(row)), chosen so that both kinds of operand reads are free of
+// bank conflicts: the A-operand read has 16 lanes on 16 consecutive rows at one
+// logical chunk (they must land in 16 different slots of a 256-byte bank window),
+// the transposing read has 16 lanes on 4 consecutive rows x 2 consecutive chunks
+// (rows r..r+3 must land in different 64-byte groups).
+template <int D> __device__ __forceinline__ int swz(int row) {
+  return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));
 }
-template <int D> __device__ __forceinline__ int swz_t(int row) {
-  return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2);
+// byte offset of element (row, d0) of a tile, d0 a multiple of 4
+template <int D> __device__ __forceinline__ uint32_t tile_off(int row, int d0) {
+  return (uint32_t)(row * BCfg<D>::ROW_BYTES + (((d0 >> 3) ^ swz<D>(row)) << 4) + ((d0 & 7) << 1));
 }
 
 // A operand slice `i` (d slice i / 2, 32-row half i % 2) of a row-major tile
 template <int D> __device__ __forceinline__ bf16x8 read_a(const char* tile, const uint32_t* rd, int i) {
   return *reinterpret_cast<const bf16x8*>(tile + rd[i >> 1] + (i & 1) * 32 * BCfg<D>::ROW_BYTES);
 }
-// transposed A operand: contraction step g (16 tile rows), d-tile t
+// transposed A operand: contraction step g (16 tile rows), d-tile t; rd[2 t] and
+// rd[2 t + 1] address the two 8-row halves of step 0
 template <int D> __device__ __forceinline__ bf16x8 read_t(const char* tile, const uint32_t* rd, int g, int t) {
-  return lds_read_tr_pair(tile + rd[t] + (16 * g) * BCfg<D>::ROW_BYTES,
-                          tile + rd[t] + (16 * g + 8) * BCfg<D>::ROW_BYTES);
+  return lds_read_tr_pair(tile + rd[2 * t] + (16 * g) * BCfg<D>::ROW_BYTES,
+                          tile + rd[2 * t + 1] + (16 * g) * BCfg<D>::ROW_BYTES);
 }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -96,13 +102,13 @@ __global__ void bwd_fill_zero_kernel(uint32_t* p, size_t n) {
 // Row-owner kernel.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_q_kernel(BwdArgs a) {
+__global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
   using C = BCfg<D>;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  char* ka_t = lds;                           // K, A-operand layout
-  char* kt_t = lds + C::TILE_BYTES;           // K, transposing-read layout
-  char* va_t = lds + 2 * C::TILE_BYTES;       // V, A-operand layout
-  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + 3 * C::TILE_BYTES);   // [64]
+  char* k_t = lds;                            // K tile
+  char* v_t = lds + C::TILE_BYTES;            // V tile
+  char* do_t = lds + 2 * C::TILE_BYTES;       // dO rows of the workgroup's 128 rows (stationary)
+  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + 4 * C::TILE_BYTES);   // [64]
   uint32_t* wvmask = wgmask + 64;                                            // [4][64]
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -123,17 +129,27 @@ __global__ __launch_bounds__(256, 1) void bwd_q_kernel(BwdArgs a) {
   const int cw = (tok_w0 < a.n_q ? tok_w0 : a.n_q - 1) / a.block;
   const bool wave_ok = tok_w0 < a.n_q;
 
-  // ---- row fragments: q and dO as B operands -------------------------------------
-  bf16x8 qf[D / 16], dof[D / 16];
+  // ---- row fragments: q (registers) and dO (LDS, each wave its own 32 rows) as B operands
+  bf16x8 qf[D / 16];
   {
     const uint16_t* qp = a.q + b * a.qs_b + my_head * a.qs_h + (int64_t)row_tok * a.qs_t + h * 8;
-    const uint16_t* dop = a.d_o + b * a.os_b + my_head * a.os_h + (int64_t)row_tok * a.os_t + h * 8;
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-      qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
-      dof[ks] = *reinterpret_cast<const bf16x8*>(dop + ks * 16);
+    for (int ks = 0; ks < D / 16; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    const u32x4 o_rs = make_rsrc(a.d_o + b * a.os_b + (int64_t)r * a.g_q * a.os_h,
+                                 ((int64_t)(a.g_q - 1) * a.os_h + ((int64_t)a.n_q - 1) * a.os_t + D) * 2);
+    constexpr int RPI = 64 / C::NCH;             // rows one copy instruction covers
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; i++) {
+      const int rw = i * RPI + lane / C::NCH;    // row of this wave
+      const int tk = min(tok_w0 + rw / a.g_q, a.n_q - 1);
+      const uint32_t voff = (uint32_t)((tk * (int)a.os_t + (rw % a.g_q) * (int)a.os_h) * 2) +
+                            (uint32_t)(((lane % C::NCH) ^ swz<D>(wave * 32 + rw)) << 4);
+      copy16_to_lds(o_rs, lds_addr_of(do_t) + (wave * 32 + i * RPI) * C::ROW_BYTES, voff, 0u);
     }
   }
+  uint32_t do_rd[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ks++) do_rd[ks] = tile_off<D>(wave * 32 + n, 16 * ks + 8 * h);
 
   // ---- chunk bitmaps ---------------------------------------------------------
   const int trk_tok = tok_w0 + lane;
@@ -188,23 +204,26 @@ __global__ __launch_bounds__(256, 1) void bwd_q_kernel(BwdArgs a) {
   const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
   const uint32_t lds0 = lds_addr_of(lds);
   const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
-  const uint32_t ka_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ swz_a<D>(c_row)) << 4));
-  const uint32_t kt_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ swz_t<D>(c_row)) << 4));
-  const uint32_t va_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ swz_a<D>(c_row)) << 4));
+  const uint32_t k_off = (uint32_t)(c_row * (int)a.ks_t * 2 + ((c_pos ^ swz<D>(c_row)) << 4));
+  const uint32_t v_off = (uint32_t)(c_row * (int)a.vs_t * 2 + ((c_pos ^ swz<D>(c_row)) << 4));
   const uint32_t k_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.ks_t * 2);
   const uint32_t v_step = (uint32_t)(C::ROWS_PER_COPY * (int)a.vs_t * 2);
 
   // ---- operand read offsets ------------------------------------------------------
+  // A operand: lane (n, h) reads logical chunk 2 ks + h of rows n, 32 + n.
+  // Transposing read: lanes 16 g' .. 16 g' + 15 serve d columns 16 (g' & 1) .. + 15
+  // of a d-tile and contraction half h = g' >> 1; lane s of the group points at
+  // tile row 4 h + s / 4 (+ 8 for the second read), d offset 16 (g' & 1) + 4 (s % 4).
   uint32_t a_rd[D / 16];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ks++)
-    a_rd[ks] = (uint32_t)(n * C::ROW_BYTES + (((2 * ks + h) ^ swz_a<D>(n)) << 4));
+  for (int ks = 0; ks < D / 16; ks++) a_rd[ks] = tile_off<D>(n, 16 * ks + 8 * h);
   const int s16 = lane & 15, a16 = (lane >> 4) & 1;
-  uint32_t t_rd[C::NDT];
+  uint32_t t_rd[2 * C::NDT];
 #pragma unroll
-  for (int t = 0; t < C::NDT; t++)
-    t_rd[t] = (uint32_t)((4 * h + (s16 >> 2)) * C::ROW_BYTES +
-                         ((((4 * t) ^ swz_t<D>(s16 >> 2)) + 2 * a16 + ((s16 & 3) >> 1)) << 4) + ((s16 & 1) << 3));
+  for (int t = 0; t < C::NDT; t++) {
+    t_rd[2 * t] = tile_off<D>(4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
+    t_rd[2 * t + 1] = tile_off<D>(8 + 4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
+  }
 
   // first pass: running max, sum of exponentials and sum of exponentials times dP;
   // D = <P, dP> = <dO, o> is taken from the latter two in fp32 (the stored bf16
@@ -229,10 +248,8 @@ __global__ __launch_bounds__(256, 1) void bwd_q_kernel(BwdArgs a) {
       __syncthreads();                      // the previous tile is no longer read
 #pragma unroll
       for (int c = 0; c < C::COPIES; c++) {
-        copy16_to_lds(k_rs, lds0 + wave * 1024 + c * 4096, ka_off, soff_k + c * k_step);
-        copy16_to_lds(v_rs, lds0 + 2 * C::TILE_BYTES + wave * 1024 + c * 4096, va_off, soff_v + c * v_step);
-        if (grad)
-          copy16_to_lds(k_rs, lds0 + C::TILE_BYTES + wave * 1024 + c * 4096, kt_off, soff_k + c * k_step);
+        copy16_to_lds(k_rs, lds0 + wave * 1024 + c * 4096, k_off, soff_k + c * k_step);
+        copy16_to_lds(v_rs, lds0 + C::TILE_BYTES + wave * 1024 + c * 4096, v_off, soff_v + c * v_step);
       }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
@@ -262,73 +279,70 @@ __global__ __launch_bounds__(256, 1) void bwd_q_kernel(BwdArgs a) {
       if (!wave_on) continue;
       const int kpos0 = cu * a.block + csub * 64;
 
-      // S^T = K Q^T
-      f32x16 s[2] = {zero16(), zero16()};
-#pragma unroll
-      for (int i = 0; i < C::NS; i++)
-        s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(ka_t, a_rd, i), qf[i >> 1], s[i & 1], 0, 0, 0);
-      // key mask: causal inside the diagonal chunk, and the end of the sequence
-      {
-        const int k0 = kpos0 + 4 * h;
-        const int lim = min(diag ? row_pos - k0 : 0x7fffffff, a.n_kv - 1 - k0);
-#pragma unroll
-        for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-          for (int j = 0; j < 16; j++) {
-            const int c = kt * 32 + (j >> 2) * 8 + (j & 3);
-            s[kt][j] = c > lim ? -INFINITY : s[kt][j];
-          }
-      }
-      // dP^T = V dO^T
-      f32x16 dp[2] = {zero16(), zero16()};
-#pragma unroll
-      for (int i = 0; i < C::NS; i++)
-        dp[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(va_t, a_rd, i), dof[i >> 1], dp[i & 1], 0, 0, 0);
-      if (!grad) {
-        float mloc = -INFINITY;
-#pragma unroll
-        for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-          for (int j = 0; j < 16; j++) mloc = fmaxf(mloc, s[kt][j]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-        const float tmax = fmaf(mloc, a.c1, bias_row);
-        const float m_new = fmaxf(m_run, tmax);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        float lsum = 0.f, dnsum = 0.f;
-#pragma unroll
-        for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-          for (int j = 0; j < 16; j++) {
-            const float e = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, bias_row - m_use));
-            lsum += e;
-            dnsum = fmaf(e, dp[kt][j], dnsum);
-          }
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
-        l_run = l_run * corr + lsum;
-        dn_run = dn_run * corr + dnsum;
-        m_run = m_new;
-        continue;
-      }
-      // dS^T = P^T (dP^T - D), packed as the B operand of the second product
-      const float off = bias_row - lse2;
+      // the tile in two halves of 32 keys (keeps one S^T and one dP^T accumulator live)
       u32x4 pb[4];
       float dssum = 0.f;
+      const float off = bias_row - lse2;
 #pragma unroll
-      for (int k = 0; k < 16; k++) {
-        const int g = k >> 2, kt = g >> 1, j = 8 * (g & 1) + 2 * (k & 3);
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[kt][j], a.c1, off));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[kt][j + 1], a.c1, off));
-        const float d0 = p0 * (dp[kt][j] - dsum);
-        const float d1 = p1 * (dp[kt][j + 1] - dsum);
-        dssum += d0 + d1;
-        pb[g][k & 3] = pack_bf16x2(d0, d1);
+      for (int kt = 0; kt < 2; kt++) {
+        // S^T = K Q^T, dP^T = V dO^T
+        f32x16 s = zero16(), dp = zero16();
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ks++) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(k_t, a_rd, 2 * ks + kt), qf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(v_t, a_rd, 2 * ks + kt),
+                                                       *reinterpret_cast<const bf16x8*>(do_t + do_rd[ks]), dp, 0, 0, 0);
+        }
+        // key mask: causal inside the diagonal chunk, and the end of the sequence
+        {
+          const int k0 = kpos0 + 32 * kt + 4 * h;
+          const int lim = min(diag ? row_pos - k0 : 0x7fffffff, a.n_kv - 1 - k0);
+#pragma unroll
+          for (int j = 0; j < 16; j++) {
+            const int c = (j >> 2) * 8 + (j & 3);
+            s[j] = c > lim ? -INFINITY : s[j];
+          }
+        }
+        if (!grad) {
+          float mloc = -INFINITY;
+#pragma unroll
+          for (int j = 0; j < 16; j++) mloc = fmaxf(mloc, s[j]);
+          mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+          const float tmax = fmaf(mloc, a.c1, bias_row);
+          const float m_new = fmaxf(m_run, tmax);
+          const float m_use = m_new == -INFINITY ? 0.f : m_new;
+          float lsum = 0.f, dnsum = 0.f;
+#pragma unroll
+          for (int j = 0; j < 16; j++) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bias_row - m_use));
+            lsum += e;
+            dnsum = fmaf(e, dp[j], dnsum);
+          }
+          const float corr = __builtin_amdgcn_exp2f(m_run - m_use);
+          l_run = l_run * corr + lsum;
+          dn_run = dn_run * corr + dnsum;
+          m_run = m_new;
+        } else {
+          // dS^T = P^T (dP^T - D), packed as the B operand of the second product
+#pragma unroll
+          for (int k = 0; k < 8; k++) {
+            const int g = 2 * kt + (k >> 2), j = 8 * (k >> 2) + 2 * (k & 3);
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, off));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(s[j + 1], a.c1, off));
+            const float d0 = p0 * (dp[j] - dsum);
+            const float d1 = p1 * (dp[j + 1] - dsum);
+            dssum += d0 + d1;
+            pb[g][k & 3] = pack_bf16x2(d0, d1);
+          }
+        }
       }
+      if (!grad) continue;
       db_acc += dssum;
       // dQ^T += K^T dS^T
 #pragma unroll
       for (int i = 0; i < C::NS; i++) {
         const int g = i / C::NDT, t = i % C::NDT;
-        dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(kt_t, t_rd, g, t),
+        dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(k_t, t_rd, g, t),
                                                            __builtin_bit_cast(bf16x8, pb[g]), dqacc[t], 0, 0, 0);
       }
       if (csub == nsub - 1) {
@@ -521,13 +535,13 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
 // Key-owner kernel: one 64-key tile per workgroup.
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
+__global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
   using C = BCfg<D>;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  char* qa_t = lds;                            // Q rows, A-operand layout
-  char* qt_t = lds + C::TILE_BYTES;            // Q rows, transposing-read layout
-  char* da_t = lds + 2 * C::TILE_BYTES;        // dO rows, A-operand layout
-  char* dt_t = lds + 3 * C::TILE_BYTES;        // dO rows, transposing-read layout
+  char* k_t = lds;                             // this workgroup's 64 keys (stationary)
+  char* v_t = lds + C::TILE_BYTES;             // and values
+  char* q_t = lds + 2 * C::TILE_BYTES;         // 64 query rows of the current step
+  char* d_t = lds + 3 * C::TILE_BYTES;         // and their dO rows
   float* lse_s = reinterpret_cast<float*>(lds + 4 * C::TILE_BYTES);   // [64] per-row scalars
   float* dsum_s = lse_s + 64;
   float* bias_s = dsum_s + 64;
@@ -545,48 +559,49 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
   const int kpos0 = ktile * 64;
   const int c = kpos0 / a.block;
   const int tok_step = 64 / a.g_q;              // tokens per 64-row step
-
-  // K and V fragments of this wave's 32 keys (B operands)
-  bf16x8 kf[D / 16], vf[D / 16];
   const int my_key = kpos0 + kh * 32 + n;
-  {
-    const bool ok = my_key < a.n_kv;
-    const uint16_t* kp = a.k + b * a.ks_b + r * a.ks_h + (int64_t)(ok ? my_key : 0) * a.ks_t + h * 8;
-    const uint16_t* vp = a.v + b * a.vs_b + r * a.vs_h + (int64_t)(ok ? my_key : 0) * a.vs_t + h * 8;
-    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-    for (int ks = 0; ks < D / 16; ks++) {
-      kf[ks] = ok ? *reinterpret_cast<const bf16x8*>(kp + ks * 16) : z;
-      vf[ks] = ok ? *reinterpret_cast<const bf16x8*>(vp + ks * 16) : z;
-    }
-  }
 
+  const u32x4 k_rs = make_rsrc(a.k + b * a.ks_b + r * a.ks_h, (((int64_t)a.n_kv - 1) * a.ks_t + D) * 2);
+  const u32x4 v_rs = make_rsrc(a.v + b * a.vs_b + r * a.vs_h, (((int64_t)a.n_kv - 1) * a.vs_t + D) * 2);
   const u32x4 q_rs = make_rsrc(a.q + b * a.qs_b + (int64_t)r * a.g_q * a.qs_h,
                                ((int64_t)(a.g_q - 1) * a.qs_h + ((int64_t)a.n_q - 1) * a.qs_t + D) * 2);
   const u32x4 o_rs = make_rsrc(a.d_o + b * a.os_b + (int64_t)r * a.g_q * a.os_h,
                                ((int64_t)(a.g_q - 1) * a.os_h + ((int64_t)a.n_q - 1) * a.os_t + D) * 2);
   const uint32_t lds0 = lds_addr_of(lds);
   const int c_row = (wave * 64 + lane) / C::NCH, c_pos = lane % C::NCH;
+  const uint32_t c_chunk = (uint32_t)((c_pos ^ swz<D>(c_row)) << 4);
   const int c_tok = c_row / a.g_q, c_head = c_row % a.g_q;
-  const uint32_t q_base = (uint32_t)((c_tok * (int)a.qs_t + c_head * (int)a.qs_h) * 2);
-  const uint32_t o_base = (uint32_t)((c_tok * (int)a.os_t + c_head * (int)a.os_h) * 2);
-  const uint32_t qa_off = q_base + ((c_pos ^ swz_a<D>(c_row)) << 4);
-  const uint32_t qt_off = q_base + ((c_pos ^ swz_t<D>(c_row)) << 4);
-  const uint32_t da_off = o_base + ((c_pos ^ swz_a<D>(c_row)) << 4);
-  const uint32_t dt_off = o_base + ((c_pos ^ swz_t<D>(c_row)) << 4);
+  const uint32_t q_off = (uint32_t)((c_tok * (int)a.qs_t + c_head * (int)a.qs_h) * 2) + c_chunk;
+  const uint32_t o_off = (uint32_t)((c_tok * (int)a.os_t + c_head * (int)a.os_h) * 2) + c_chunk;
   const uint32_t q_step = (uint32_t)((C::ROWS_PER_COPY / a.g_q) * (int)a.qs_t * 2);
   const uint32_t o_step = (uint32_t)((C::ROWS_PER_COPY / a.g_q) * (int)a.os_t * 2);
+  // the key and value tiles, once (rows past the end of the sequence read as zeros)
+  {
+    const uint32_t k_off = (uint32_t)(c_row * (int)a.ks_t * 2) + c_chunk;
+    const uint32_t v_off = (uint32_t)(c_row * (int)a.vs_t * 2) + c_chunk;
+#pragma unroll
+    for (int i = 0; i < C::COPIES; i++) {
+      const uint32_t la = lds0 + wave * 1024 + i * 4096;
+      copy16_to_lds(k_rs, la, k_off, (uint32_t)(kpos0 + i * C::ROWS_PER_COPY) * (uint32_t)a.ks_t * 2u);
+      copy16_to_lds(v_rs, la + C::TILE_BYTES, v_off, (uint32_t)(kpos0 + i * C::ROWS_PER_COPY) * (uint32_t)a.vs_t * 2u);
+    }
+  }
 
-  uint32_t a_rd[D / 16];
+  // operand read offsets: B operands (keys kh*32 + n) and A operands (rows rh*32 + n)
+  // share the row-major pattern; the transposing reads walk this wave's 32 rows
+  uint32_t b_rd[D / 16], a_rd[D / 16];
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ks++)
-    a_rd[ks] = (uint32_t)((rh * 32 + n) * C::ROW_BYTES + (((2 * ks + h) ^ swz_a<D>(n)) << 4));
+  for (int ks = 0; ks < D / 16; ks++) {
+    b_rd[ks] = tile_off<D>(kh * 32 + n, 16 * ks + 8 * h);
+    a_rd[ks] = tile_off<D>(rh * 32 + n, 16 * ks + 8 * h);
+  }
   const int s16 = lane & 15, a16 = (lane >> 4) & 1;
-  uint32_t t_rd[C::NDT];
+  uint32_t t_rd[2 * C::NDT];
 #pragma unroll
-  for (int t = 0; t < C::NDT; t++)
-    t_rd[t] = (uint32_t)((rh * 32 + 4 * h + (s16 >> 2)) * C::ROW_BYTES +
-                         ((((4 * t) ^ swz_t<D>(s16 >> 2)) + 2 * a16 + ((s16 & 3) >> 1)) << 4) + ((s16 & 1) << 3));
+  for (int t = 0; t < C::NDT; t++) {
+    t_rd[2 * t] = tile_off<D>(rh * 32 + 4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
+    t_rd[2 * t + 1] = tile_off<D>(rh * 32 + 8 + 4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
+  }
 
   f32x16 dkacc[C::NDT], dvacc[C::NDT];
 #pragma unroll
@@ -604,8 +619,9 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
         if (tok0 >= a.n_q) continue;
         __syncthreads();                    // the previous step is no longer read
         int have = 0;
-        if (tid < 64) {
-          const int tk = tok0 + tid / a.g_q, head = r * a.g_q + tid % a.g_q;
+        if (lane < 16) {
+          const int row = wave * 16 + lane;
+          const int tk = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
           const bool ok = tk < a.n_q;
           const int tkc = ok ? tk : a.n_q - 1;
           const int64_t trow = ((int64_t)b * a.h_kv + r) * a.n_q + tkc;
@@ -619,11 +635,11 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
             bv = isdiag ? 0.f : a.biasd[trow * a.t_all + c] * kLog2e;
             if (c < n_cand) dx = a.dxd[hrow * a.t_all + c];
           }
-          bias_s[tid] = bv;
-          dx_s[tid] = dx;
-          lse_s[tid] = a.lse[hrow];
-          dsum_s[tid] = a.dsum[hrow];
-          pos_s[tid] = a.causal ? tkc : 0x7fffffff;
+          bias_s[row] = bv;
+          dx_s[row] = dx;
+          lse_s[row] = a.lse[hrow];
+          dsum_s[row] = a.dsum[hrow];
+          pos_s[row] = a.causal ? tkc : 0x7fffffff;
           have = bit ? 1 : 0;
         }
         if (!__syncthreads_or(have)) continue;
@@ -631,11 +647,9 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
         const uint32_t soff_o = (uint32_t)tok0 * (uint32_t)a.os_t * 2u;
 #pragma unroll
         for (int i = 0; i < C::COPIES; i++) {
-          const uint32_t la = lds0 + wave * 1024 + i * 4096;
-          copy16_to_lds(q_rs, la, qa_off, soff_q + i * q_step);
-          copy16_to_lds(q_rs, la + C::TILE_BYTES, qt_off, soff_q + i * q_step);
-          copy16_to_lds(o_rs, la + 2 * C::TILE_BYTES, da_off, soff_o + i * o_step);
-          copy16_to_lds(o_rs, la + 3 * C::TILE_BYTES, dt_off, soff_o + i * o_step);
+          const uint32_t la = lds0 + 2 * C::TILE_BYTES + wave * 1024 + i * 4096;
+          copy16_to_lds(q_rs, la, q_off, soff_q + i * q_step);
+          copy16_to_lds(o_rs, la + C::TILE_BYTES, o_off, soff_o + i * o_step);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -644,8 +658,10 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
         f32x16 s = zero16(), dp = zero16();
 #pragma unroll
         for (int ks = 0; ks < D / 16; ks++) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(qa_t + a_rd[ks]), kf[ks], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(da_t + a_rd[ks]), vf[ks], dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(q_t + a_rd[ks]),
+                                                      *reinterpret_cast<const bf16x8*>(k_t + b_rd[ks]), s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(d_t + a_rd[ks]),
+                                                       *reinterpret_cast<const bf16x8*>(v_t + b_rd[ks]), dp, 0, 0, 0);
         }
         u32x4 pp[2], pd[2];
 #pragma unroll
@@ -677,9 +693,9 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
         for (int g = 0; g < 2; g++)
 #pragma unroll
           for (int t = 0; t < C::NDT; t++) {
-            dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(dt_t, t_rd, g, t),
+            dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(d_t, t_rd, g, t),
                                                                __builtin_bit_cast(bf16x8, pp[g]), dvacc[t], 0, 0, 0);
-            dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(qt_t, t_rd, g, t),
+            dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(q_t, t_rd, g, t),
                                                                __builtin_bit_cast(bf16x8, pd[g]), dkacc[t], 0, 0, 0);
           }
         // dkbar += sum_rows dx q: thread (wave, lane) takes d = 2 lane, 2 lane + 1 and rows 16 wave ..
@@ -688,8 +704,7 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
           for (int rr = 0; rr < 16; rr++) {
             const int row = wave * 16 + rr;
             const float dx = dx_s[row];
-            const uint32_t w = *reinterpret_cast<const uint32_t*>(
-                qa_t + row * C::ROW_BYTES + ((((2 * lane) >> 3) ^ swz_a<D>(row)) << 4) + ((2 * lane) & 7) * 2);
+            const uint32_t w = *reinterpret_cast<const uint32_t*>(q_t + tile_off<D>(row, 2 * lane));
             kb0 = fmaf(dx, bf16_lo(w), kb0);
             kb1 = fmaf(dx, bf16_hi(w), kb1);
           }
@@ -699,6 +714,7 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_kernel(BwdArgs a) {
   }
 
   // ---- combine the two row halves and write ------------------------------------
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup without any step: its K / V copies
   __syncthreads();
   if (2 * lane < D) { red[wave * D + 2 * lane] = kb0; red[wave * D + 2 * lane + 1] = kb1; }
   float* xch = reinterpret_cast<float*>(lds);          // [2 kh][2 tensors][NDT*16][64 lanes]
@@ -782,7 +798,7 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
-    const size_t lds = 3 * C::TILE_BYTES + 5 * 64 * 4;
+    const size_t lds = 4 * C::TILE_BYTES + 5 * 64 * 4;
     auto kern = bwd_q_kernel<D>;
     if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
       return e;
