@@ -608,43 +608,73 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
   for (int t = 0; t < C::NDT; t++) { dkacc[t] = zero16(); dvacc[t] = zero16(); }
   float kb0 = 0.f, kb1 = 0.f;      // dkbar partial of this thread's d pair over its 16 rows per step
 
+  // Steps: the 64-row halves of the row tiles whose bit is set in this chunk's column
+  // mask, ascending.  The per-row scalars of a step (mask bit, bias, dx, log-sum-exp,
+  // D) are fetched one step ahead into registers, all addresses known up front, so
+  // that their latency overlaps the previous step instead of preceding the tile copies.
   const uint32_t* cm = a.colmask + ((int64_t)hbi * a.t_all + c) * a.cwords;
-  for (int wi = 0; wi < a.cwords; wi++) {
-    uint32_t bits = __builtin_amdgcn_readfirstlane(cm[wi]);
-    while (bits) {
-      const int T = wi * 32 + __builtin_ctz(bits);
-      bits &= bits - 1u;
-      for (int half = 0; half < 2; half++) {
-        const int tok0 = T * 2 * tok_step + half * tok_step;
-        if (tok0 >= a.n_q) continue;
+  int st_wi = -1, st_half = 1, st_T = 0;
+  uint32_t st_bits = 0u;
+  auto next_step = [&]() -> int {        // first token of the next step, or -1
+    for (;;) {
+      if (st_half == 0) { st_half = 1; }
+      else {
+        while (st_bits == 0u) {
+          if (++st_wi >= a.cwords) return -1;
+          st_bits = __builtin_amdgcn_readfirstlane(cm[st_wi]);
+        }
+        st_T = st_wi * 32 + __builtin_ctz(st_bits);
+        st_bits &= st_bits - 1u;
+        st_half = 0;
+      }
+      const int t0 = st_T * 2 * tok_step + st_half * tok_step;
+      if (t0 < a.n_q) return t0;
+    }
+  };
+  // this lane's row of a step (lanes 0..15 of each wave: row 16 wave + lane)
+  const int s_row = wave * 16 + (lane & 15);
+  const int s_head = r * a.g_q + s_row % a.g_q;
+  uint32_t f_mask = 0u;
+  float f_bias = 0.f, f_dx = 0.f, f_lse = 0.f, f_dsum = 0.f;
+  int f_tok = 0;
+  bool f_ok = false;
+  auto fetch = [&](int t0) {
+    const int tk = t0 + s_row / a.g_q;
+    f_ok = tk < a.n_q;
+    f_tok = f_ok ? tk : a.n_q - 1;
+    const int64_t trow = ((int64_t)b * a.h_kv + r) * a.n_q + f_tok;
+    const int64_t hrow = ((int64_t)b * a.h_q + s_head) * a.n_q + f_tok;
+    f_mask = a.mask[trow * a.words + (c >> 5)];
+    f_bias = a.biasd[trow * a.t_all + c];      // meaningful only where the mask bit is set
+    f_dx = a.dxd[hrow * a.t_all + c];          // and, for dx, where the chunk is a candidate
+    f_lse = a.lse[hrow];
+    f_dsum = a.dsum[hrow];
+  };
+  int tok0 = next_step();
+  if (tok0 >= 0 && lane < 16) fetch(tok0);
+  while (tok0 >= 0) {
+    {
+      {
         __syncthreads();                    // the previous step is no longer read
         int have = 0;
         if (lane < 16) {
-          const int row = wave * 16 + lane;
-          const int tk = tok0 + row / a.g_q, head = r * a.g_q + row % a.g_q;
-          const bool ok = tk < a.n_q;
-          const int tkc = ok ? tk : a.n_q - 1;
-          const int64_t trow = ((int64_t)b * a.h_kv + r) * a.n_q + tkc;
-          const int64_t hrow = ((int64_t)b * a.h_q + head) * a.n_q + tkc;
-          const bool bit = ok && ((a.mask[trow * a.words + (c >> 5)] >> (c & 31)) & 1u);
-          const int cdiag = tkc / a.block;
+          const bool bit = f_ok && ((f_mask >> (c & 31)) & 1u);
+          const int cdiag = f_tok / a.block;
           const bool isdiag = a.causal && c == cdiag;
           const int n_cand = a.causal ? max(cdiag - a.window, 0) : a.t_c;
-          float bv = -INFINITY, dx = 0.f;
-          if (bit) {
-            bv = isdiag ? 0.f : a.biasd[trow * a.t_all + c] * kLog2e;
-            if (c < n_cand) dx = a.dxd[hrow * a.t_all + c];
-          }
-          bias_s[row] = bv;
-          dx_s[row] = dx;
-          lse_s[row] = a.lse[hrow];
-          dsum_s[row] = a.dsum[hrow];
-          pos_s[row] = a.causal ? tkc : 0x7fffffff;
+          bias_s[s_row] = bit ? (isdiag ? 0.f : f_bias * kLog2e) : -INFINITY;
+          dx_s[s_row] = (bit && c < n_cand) ? f_dx : 0.f;
+          lse_s[s_row] = f_lse;
+          dsum_s[s_row] = f_dsum;
+          pos_s[s_row] = a.causal ? f_tok : 0x7fffffff;
           have = bit ? 1 : 0;
         }
+        const int cur_tok0 = tok0;
+        tok0 = next_step();
+        if (tok0 >= 0 && lane < 16) fetch(tok0);
         if (!__syncthreads_or(have)) continue;
-        const uint32_t soff_q = (uint32_t)tok0 * (uint32_t)a.qs_t * 2u;
-        const uint32_t soff_o = (uint32_t)tok0 * (uint32_t)a.os_t * 2u;
+        const uint32_t soff_q = (uint32_t)cur_tok0 * (uint32_t)a.qs_t * 2u;
+        const uint32_t soff_o = (uint32_t)cur_tok0 * (uint32_t)a.os_t * 2u;
 #pragma unroll
         for (int i = 0; i < C::COPIES; i++) {
           const uint32_t la = lds0 + 2 * C::TILE_BYTES + wave * 1024 + i * 4096;
