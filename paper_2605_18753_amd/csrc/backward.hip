@@ -77,15 +77,25 @@ template <int D> __device__ __forceinline__ uint32_t tile_off(int row, int d0) {
   return (uint32_t)(row * BCfg<D>::ROW_BYTES + (((d0 >> 3) ^ swz<D>(row)) << 4) + ((d0 & 7) << 1));
 }
 
-// A operand slice `i` (d slice i / 2, 32-row half i % 2) of a row-major tile
-template <int D> __device__ __forceinline__ bf16x8 read_a(const char* tile, const uint32_t* rd, int i) {
-  return *reinterpret_cast<const bf16x8*>(tile + rd[i >> 1] + (i & 1) * 32 * BCfg<D>::ROW_BYTES);
+// Operand addresses.  Because the chunk permutation is an XOR, the offsets of the
+// d slices of one row differ from the first one by an XOR with a constant, so a
+// lane keeps one base offset per kind of read instead of one register per slice.
+// A operand slice `i` (d slice ks = i / 2, 32-row half i % 2) of a row-major tile;
+// base = tile_off(row, 8 h): the slice starts at d = 16 ks + 8 h, chunk 2 ks + h
+template <int D> __device__ __forceinline__ bf16x8 read_a(const char* tile, uint32_t base, int i) {
+  return *reinterpret_cast<const bf16x8*>(tile + (base ^ (uint32_t)((i >> 1) << 5)) + (i & 1) * 32 * BCfg<D>::ROW_BYTES);
 }
-// transposed A operand: contraction step g (16 tile rows), d-tile t; rd[2 t] and
-// rd[2 t + 1] address the two 8-row halves of step 0
-template <int D> __device__ __forceinline__ bf16x8 read_t(const char* tile, const uint32_t* rd, int g, int t) {
-  return lds_read_tr_pair(tile + rd[2 * t] + (16 * g) * BCfg<D>::ROW_BYTES,
-                          tile + rd[2 * t + 1] + (16 * g) * BCfg<D>::ROW_BYTES);
+// transposed A operand: contraction step g (16 tile rows), d-tile t; lo / hi address the
+// two 8-row halves of step 0 at d-tile 0 (d-tile t starts 4 t chunks further)
+template <int D> __device__ __forceinline__ bf16x8 read_t(const char* tile, uint32_t lo, uint32_t hi, int g, int t) {
+  return lds_read_tr_pair(tile + (lo ^ (uint32_t)(t << 6)) + (16 * g) * BCfg<D>::ROW_BYTES,
+                          tile + (hi ^ (uint32_t)(t << 6)) + (16 * g) * BCfg<D>::ROW_BYTES);
+}
+
+// two fp32 -> packed bf16 (round to nearest even) with the hardware conversion
+__device__ __forceinline__ uint32_t cvt_bf16x2(float lo, float hi) {
+  const bf16x2 w = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, w);
 }
 
 __device__ __forceinline__ f32x16 zero16() {
@@ -147,9 +157,7 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
       copy16_to_lds(o_rs, lds_addr_of(do_t) + (wave * 32 + i * RPI) * C::ROW_BYTES, voff, 0u);
     }
   }
-  uint32_t do_rd[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ks++) do_rd[ks] = tile_off<D>(wave * 32 + n, 16 * ks + 8 * h);
+  const uint32_t do_rd = tile_off<D>(wave * 32 + n, 8 * h);
 
   // ---- chunk bitmaps ---------------------------------------------------------
   const int trk_tok = tok_w0 + lane;
@@ -214,16 +222,10 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
   // Transposing read: lanes 16 g' .. 16 g' + 15 serve d columns 16 (g' & 1) .. + 15
   // of a d-tile and contraction half h = g' >> 1; lane s of the group points at
   // tile row 4 h + s / 4 (+ 8 for the second read), d offset 16 (g' & 1) + 4 (s % 4).
-  uint32_t a_rd[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ks++) a_rd[ks] = tile_off<D>(n, 16 * ks + 8 * h);
+  const uint32_t a_rd = tile_off<D>(n, 8 * h);
   const int s16 = lane & 15, a16 = (lane >> 4) & 1;
-  uint32_t t_rd[2 * C::NDT];
-#pragma unroll
-  for (int t = 0; t < C::NDT; t++) {
-    t_rd[2 * t] = tile_off<D>(4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
-    t_rd[2 * t + 1] = tile_off<D>(8 + 4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
-  }
+  const uint32_t t_lo = tile_off<D>(4 * h + (s16 >> 2), 16 * a16 + 4 * (s16 & 3));
+  const uint32_t t_hi = tile_off<D>(8 + 4 * h + (s16 >> 2), 16 * a16 + 4 * (s16 & 3));
 
   // first pass: running max, sum of exponentials and sum of exponentials times dP;
   // D = <P, dP> = <dO, o> is taken from the latter two in fp32 (the stored bf16
@@ -291,10 +293,10 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
         for (int ks = 0; ks < D / 16; ks++) {
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(k_t, a_rd, 2 * ks + kt), qf[ks], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(v_t, a_rd, 2 * ks + kt),
-                                                       *reinterpret_cast<const bf16x8*>(do_t + do_rd[ks]), dp, 0, 0, 0);
+                                                       read_a<D>(do_t, do_rd, 2 * ks), dp, 0, 0, 0);
         }
         // key mask: causal inside the diagonal chunk, and the end of the sequence
-        {
+        if (diag || kpos0 + 64 > a.n_kv) {
           const int k0 = kpos0 + 32 * kt + 4 * h;
           const int lim = min(diag ? row_pos - k0 : 0x7fffffff, a.n_kv - 1 - k0);
 #pragma unroll
@@ -332,7 +334,7 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
             const float d0 = p0 * (dp[j] - dsum);
             const float d1 = p1 * (dp[j + 1] - dsum);
             dssum += d0 + d1;
-            pb[g][k & 3] = pack_bf16x2(d0, d1);
+            pb[g][k & 3] = cvt_bf16x2(d0, d1);
           }
         }
       }
@@ -342,7 +344,7 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
 #pragma unroll
       for (int i = 0; i < C::NS; i++) {
         const int g = i / C::NDT, t = i % C::NDT;
-        dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(k_t, t_rd, g, t),
+        dqacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(k_t, t_lo, t_hi, g, t),
                                                            __builtin_bit_cast(bf16x8, pb[g]), dqacc[t], 0, 0, 0);
       }
       if (csub == nsub - 1) {
@@ -437,29 +439,43 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
     for (int e = lane; e < n_r; e += 64) dsum += dbrow[cidx[e]];
     const float dmean = wave_sum(dsum) / (float)n_r;
 
-    // sweep A: scores, weights, slopes; S0 = sum g, S1 = sum g dw_hat per head
+    // sweep A: scores, weights, slopes; S0 = sum g, S1 = sum g dw_hat per head.
+    // Eight lanes share a routed chunk (lane = 8 cs + dp): lane dp reads the dp-th
+    // eighth of the summary row, so a wave instruction covers 8 whole rows, and the
+    // partial dot products are combined over the 8 lanes by DPP.  Every lane of the
+    // group then holds all scores; lane dp keeps the per-head results of the heads
+    // hh = dp (mod 8) (slopes to memory, their sums in registers).
+    constexpr int DP = D / 8;                      // d range of one lane
+    const int cs = lane >> 3, dp = lane & 7;
     float s0[G], s1[G];
 #pragma unroll
     for (int hh = 0; hh < G; hh++) s0[hh] = s1[hh] = 0.f;
-    for (int e = lane; e < n_r; e += 64) {
-      const int c = cidx[e];
-      const float4* krow = reinterpret_cast<const float4*>(kb + (int64_t)c * D);
+    for (int e0 = 0; e0 < n_r; e0 += 8) {
+      const int e = e0 + cs;
+      const bool live = e < n_r;
+      const int c = cidx[live ? e : n_r - 1];
+      const float4* krow = reinterpret_cast<const float4*>(kb + (int64_t)c * D + dp * DP);
       float x[G];
 #pragma unroll
       for (int hh = 0; hh < G; hh++) x[hh] = 0.f;
-#pragma unroll 2
-      for (int d4 = 0; d4 < D / 4; d4++) {
+#pragma unroll
+      for (int d4 = 0; d4 < DP / 4; d4++) {
         const float4 kv = krow[d4];
 #pragma unroll
         for (int hh = 0; hh < G; hh++) {
-          const float4 qv = *reinterpret_cast<const float4*>(qs + hh * D + d4 * 4);
+          const float4 qv = *reinterpret_cast<const float4*>(qs + hh * D + dp * DP + d4 * 4);
           x[hh] = fmaf(qv.x, kv.x, fmaf(qv.y, kv.y, fmaf(qv.z, kv.z, fmaf(qv.w, kv.w, x[hh]))));
         }
       }
       float gd[G], wsum = 0.f;
 #pragma unroll
       for (int hh = 0; hh < G; hh++) {
-        const float u = x[hh] * a.xscale - tauh[hh];
+        float xs = x[hh];
+        asm volatile("" : "+v"(xs));
+        xs += dpp_f<0xB1>(xs);     // lane ^ 1
+        xs += dpp_f<0x4E>(xs);     // lane ^ 2
+        xs += dpp_f<0x141>(xs);    // the other quad of the 8 lanes
+        const float u = xs * a.xscale - tauh[hh];
         float wv = 0.f;
         gd[hh] = 0.f;
         if (u > 0.f) pow_and_slope(u, a.pexp, wv, gd[hh]);
@@ -467,12 +483,15 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
       }
       // dw_hat = dlnw / w / g_q with w = wsum / g_q
       const float dwh = wsum > 0.f ? (dbrow[c] - dmean) / (a.sigma * wsum) : 0.f;
-      dwl[e] = dwh;
+      if (live) {
+        if (dp == 0) dwl[e] = dwh;
 #pragma unroll
-      for (int hh = 0; hh < G; hh++) {
-        s0[hh] += gd[hh];
-        s1[hh] += gd[hh] * dwh;
-        a.dxd[(((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c] = gd[hh];
+        for (int hh = 0; hh < G; hh++)
+          if ((hh & 7) == dp) {
+            s0[hh] += gd[hh];
+            s1[hh] += gd[hh] * dwh;
+            a.dxd[(((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c] = gd[hh];
+          }
       }
     }
     float ratio[G];
@@ -481,19 +500,24 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
       const float t0 = wave_sum(s0[hh]), t1 = wave_sum(s1[hh]);
       ratio[hh] = t0 > 0.f ? t1 / t0 : 0.f;
     }
-    // sweep B, one segment of SEG routed chunks at a time: dx, then dq += dx kbar
+    // sweep B, one segment of SEG routed chunks at a time: dx (each lane turns the slopes
+    // it wrote itself into dx), then dq += dx kbar with the lanes over d
     for (int e0 = 0; e0 < n_r; e0 += SEG) {
-      const int e = e0 + lane;
       __syncthreads();
-      if (e < n_r) {
-        const int c = cidx[e];
-        const float dwh = dwl[e];
 #pragma unroll
-        for (int hh = 0; hh < G; hh++) {
-          float* px = a.dxd + (((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c;
-          const float dx = *px * (dwh - ratio[hh]);
-          *px = dx;
-          dxs[hh * SEG + lane] = dx;
+      for (int it = 0; it < SEG / 8; it++) {
+        const int j = it * 8 + cs, e = e0 + j;
+        if (e < n_r) {
+          const int c = cidx[e];
+          const float dwh = dwl[e];
+#pragma unroll
+          for (int hh = 0; hh < G; hh++)
+            if ((hh & 7) == dp) {
+              float* px = a.dxd + (((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c;
+              const float dx = *px * (dwh - ratio[hh]);
+              *px = dx;
+              dxs[hh * SEG + j] = dx;
+            }
         }
       }
       __syncthreads();
@@ -524,7 +548,7 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
     if (D == 128) {
       const float2 base = *reinterpret_cast<const float2*>(a.dq32 + row * D + 2 * lane);
       *reinterpret_cast<uint32_t*>(out + 2 * lane) =
-          pack_bf16x2(fmaf(a.xscale, acc_q[hh][0], base.x), fmaf(a.xscale, acc_q[hh][1], base.y));
+          cvt_bf16x2(fmaf(a.xscale, acc_q[hh][0], base.x), fmaf(a.xscale, acc_q[hh][1], base.y));
     } else {
       out[lane] = (uint16_t)f32_to_bf16_bits(fmaf(a.xscale, acc_q[hh][0], a.dq32[row * D + lane]));
     }
@@ -589,19 +613,10 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
 
   // operand read offsets: B operands (keys kh*32 + n) and A operands (rows rh*32 + n)
   // share the row-major pattern; the transposing reads walk this wave's 32 rows
-  uint32_t b_rd[D / 16], a_rd[D / 16];
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ks++) {
-    b_rd[ks] = tile_off<D>(kh * 32 + n, 16 * ks + 8 * h);
-    a_rd[ks] = tile_off<D>(rh * 32 + n, 16 * ks + 8 * h);
-  }
+  const uint32_t b_rd = tile_off<D>(kh * 32 + n, 8 * h), a_rd = tile_off<D>(rh * 32 + n, 8 * h);
   const int s16 = lane & 15, a16 = (lane >> 4) & 1;
-  uint32_t t_rd[2 * C::NDT];
-#pragma unroll
-  for (int t = 0; t < C::NDT; t++) {
-    t_rd[2 * t] = tile_off<D>(rh * 32 + 4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
-    t_rd[2 * t + 1] = tile_off<D>(rh * 32 + 8 + 4 * h + (s16 >> 2), 32 * t + 16 * a16 + 4 * (s16 & 3));
-  }
+  const uint32_t t_lo = tile_off<D>(rh * 32 + 4 * h + (s16 >> 2), 16 * a16 + 4 * (s16 & 3));
+  const uint32_t t_hi = tile_off<D>(rh * 32 + 8 + 4 * h + (s16 >> 2), 16 * a16 + 4 * (s16 & 3));
 
   f32x16 dkacc[C::NDT], dvacc[C::NDT];
 #pragma unroll
@@ -673,6 +688,13 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
         tok0 = next_step();
         if (tok0 >= 0 && lane < 16) fetch(tok0);
         if (!__syncthreads_or(have)) continue;
+        // is the chunk a routing candidate of any row of this step?  (the candidate count
+        // grows with the position, so the step's last token decides)
+        const bool any_cand = c < (a.causal ? max(min(cur_tok0 + tok_step - 1, a.n_q - 1) / a.block - a.window, 0)
+                                            : a.t_c);
+        // the key mask matters only where the rows' own chunk is this one, or at the end of the sequence
+        const bool masked = (a.causal && (cur_tok0 + tok_step - 1) / a.block >= c && cur_tok0 / a.block <= c) ||
+                            kpos0 + 64 > a.n_kv;
         const uint32_t soff_q = (uint32_t)cur_tok0 * (uint32_t)a.qs_t * 2u;
         const uint32_t soff_o = (uint32_t)cur_tok0 * (uint32_t)a.os_t * 2u;
 #pragma unroll
@@ -685,13 +707,15 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
         __syncthreads();
 
         // S = Q K^T and dP = dO V^T for this wave's 32 rows x 32 keys
+        // (the base offsets are made opaque here so that the per-slice offsets derived from
+        // them are formed next to their use instead of being kept in registers across steps)
+        uint32_t a_b = a_rd, b_b = b_rd, tl = t_lo, th = t_hi;
+        asm volatile("" : "+v"(a_b), "+v"(b_b), "+v"(tl), "+v"(th));
         f32x16 s = zero16(), dp = zero16();
 #pragma unroll
         for (int ks = 0; ks < D / 16; ks++) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(q_t + a_rd[ks]),
-                                                      *reinterpret_cast<const bf16x8*>(k_t + b_rd[ks]), s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(d_t + a_rd[ks]),
-                                                       *reinterpret_cast<const bf16x8*>(v_t + b_rd[ks]), dp, 0, 0, 0);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(q_t, a_b, 2 * ks), read_a<D>(k_t, b_b, 2 * ks), s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(d_t, a_b, 2 * ks), read_a<D>(v_t, b_b, 2 * ks), dp, 0, 0, 0);
         }
         u32x4 pp[2], pd[2];
 #pragma unroll
@@ -708,29 +732,29 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
 #pragma unroll
           for (int i = 0; i < 4; i++) {
             const int j = q4 * 4 + i;
-            const bool dead = my_key > ps[i] || my_key >= a.n_kv;
+            const bool dead = masked && (my_key > ps[i] || my_key >= a.n_kv);
             const float p = dead ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bs[i] - ls[i]));
             pv[i] = p;
             dv[i] = p * (dp[j] - ds[i]);
           }
-          pp[q4 >> 1][(q4 & 1) * 2 + 0] = pack_bf16x2(pv[0], pv[1]);
-          pp[q4 >> 1][(q4 & 1) * 2 + 1] = pack_bf16x2(pv[2], pv[3]);
-          pd[q4 >> 1][(q4 & 1) * 2 + 0] = pack_bf16x2(dv[0], dv[1]);
-          pd[q4 >> 1][(q4 & 1) * 2 + 1] = pack_bf16x2(dv[2], dv[3]);
+          pp[q4 >> 1][(q4 & 1) * 2 + 0] = cvt_bf16x2(pv[0], pv[1]);
+          pp[q4 >> 1][(q4 & 1) * 2 + 1] = cvt_bf16x2(pv[2], pv[3]);
+          pd[q4 >> 1][(q4 & 1) * 2 + 0] = cvt_bf16x2(dv[0], dv[1]);
+          pd[q4 >> 1][(q4 & 1) * 2 + 1] = cvt_bf16x2(dv[2], dv[3]);
         }
         // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over this wave's 32 rows)
 #pragma unroll
         for (int g = 0; g < 2; g++)
 #pragma unroll
           for (int t = 0; t < C::NDT; t++) {
-            dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(d_t, t_rd, g, t),
+            dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(d_t, tl, th, g, t),
                                                                __builtin_bit_cast(bf16x8, pp[g]), dvacc[t], 0, 0, 0);
-            dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(q_t, t_rd, g, t),
+            dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(q_t, tl, th, g, t),
                                                                __builtin_bit_cast(bf16x8, pd[g]), dkacc[t], 0, 0, 0);
           }
         // dkbar += sum_rows dx q: thread (wave, lane) takes d = 2 lane, 2 lane + 1 and rows 16 wave ..
-        if (2 * lane < D) {
-#pragma unroll 4
+        if (any_cand && 2 * lane < D) {
+#pragma unroll 2
           for (int rr = 0; rr < 16; rr++) {
             const int row = wave * 16 + rr;
             const float dx = dx_s[row];
@@ -777,9 +801,9 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
           vv[i] = dvacc[t][j] + xch[((kh * 2 + 1) * C::NDT * 16 + t * 16 + j) * 64 + lane];
         }
         uint2 w;
-        w.x = pack_bf16x2(kv[0], kv[1]); w.y = pack_bf16x2(kv[2], kv[3]);
+        w.x = cvt_bf16x2(kv[0], kv[1]); w.y = cvt_bf16x2(kv[2], kv[3]);
         *reinterpret_cast<uint2*>(dkp + d0) = w;
-        w.x = pack_bf16x2(vv[0], vv[1]); w.y = pack_bf16x2(vv[2], vv[3]);
+        w.x = cvt_bf16x2(vv[0], vv[1]); w.y = cvt_bf16x2(vv[2], vv[3]);
         *reinterpret_cast<uint2*>(dvp + d0) = w;
       }
   }
