@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--backward-only", action="store_true",
+                    help="time only the forward + backward of the training-shaped workload and print its JSON line "
+                         "(the command of the backward kernels' rocprofv3 summaries)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--small", action="store_true", help="shrunken shapes (debugging)")
     ap.add_argument("--paper-protocol", action="store_true",
@@ -338,6 +341,16 @@ def main():
         print(json.dumps({"metric": "Stage-2 speed-up over the in-library dense attention, randomised chunk masks "
                                     "(kernel-benchmark protocol of the paper)", "unit": "x", "n_gpus": 1,
                           "data": "synthetic", "dtype": "bf16", **res}))
+        return
+    if a.backward_only:
+        wb = C5.replace(n_q=2048, n_kv=2048, batch=1, name="C5_small") if a.small else C5
+        r = bench_backward(wb, a.steps, a.warmup, torch, B, make_inputs)
+        flops = 2.5 * r["f_alg"]
+        print(json.dumps({"metric": "backward algorithmic TFLOP/s (5 matrix products per attended query-key pair)",
+                          "value": flops / (r["ms_backward"] * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
+                          "steps": a.steps, "warmup": a.warmup, "ms_per_step": r["ms_backward"], "dtype": "bf16",
+                          "data": "synthetic", "config": {"workload": wb.name}, "ms_forward": r["ms_forward"],
+                          "chunk_sparsity": r["sparsity"], "f_alg_forward": r["f_alg"]}))
         return
     if a.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
