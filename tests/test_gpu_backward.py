@@ -106,3 +106,92 @@ def test_backward_matches_the_oracle(case):
                 share = np.abs(ref[1] - direct).max(axis=-1) / np.maximum(rowmax, 0.1 * np.median(rowmax))
                 assert share.max() > 0.05, share.max()
     print(f"{name}: worst row-relative error dq {worst['dq']:.2e} dk {worst['dk']:.2e} dv {worst['dv']:.2e}")
+
+
+def test_backward_token_major_layout_and_workspace_reuse():
+    """q, k, v, dO and the gradients in [batch, token, head, d] storage (head stride d,
+    token stride heads*d), and a second call on the same workspace with other
+    inputs: the results must equal those of contiguous tensors / a fresh workspace."""
+    w = Workload("bwd_layout", 2, 8, 2, 640, 640, 128, 64, seed=23, offset_sigma=0.8)
+    q, k, v = gen(w)
+    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16).to(DEV)
+    run = U.run_prefill(w, q, k, v)
+    ref = run_backward(w, q, k, v, run, d_o)
+
+    def token_major(t):
+        return t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)      # same values, [b, n, h, d] storage
+
+    qt, kt, vt, dot = (token_major(t) for t in (q, k, v, d_o))
+    ot = token_major(torch.empty_like(q))
+    p = B.make_params(qt, kt, vt, ot, w.block, w.alpha, w.gamma, w.sigma, w.causal)
+    assert p.q_stride[1] == w.head_dim and p.q_stride[2] == w.h_q * w.head_dim
+    dq, dk, dv = (token_major(torch.full_like(t, float("nan"))) for t in (q, k, v))
+    ws = B.alloc_backward_workspace(p, DEV)
+    B.dash_attn_backward(p, qt, kt, vt, dot, run.kbar, run.lists, dq, dk, dv, ws)
+    torch.cuda.synchronize()
+    for got, want in zip((dq, dk, dv), ref):
+        assert torch.equal(got, want)
+
+    # other inputs through the same workspace (the column masks of the first call must not leak)
+    w2 = w.replace(seed=24, gamma=2.0)
+    q2, k2, v2 = gen(w2)
+    run2 = U.run_prefill(w2, q2, k2, v2)
+    ref2 = run_backward(w2, q2, k2, v2, run2, d_o)
+    dq2, dk2, dv2 = torch.empty_like(q2), torch.empty_like(k2), torch.empty_like(v2)
+    B.dash_attn_backward(run2.params, q2, k2, v2, d_o, run2.kbar, run2.lists, dq2, dk2, dv2, ws)
+    torch.cuda.synchronize()
+    for got, want in zip((dq2, dk2, dv2), ref2):
+        assert torch.equal(got, want)
+
+
+def test_backward_at_the_benchmark_shape_on_sampled_rows():
+    """The training-shaped workload in the launch configuration bench.py times: dq of
+    sampled query rows and dk, dv of the keys of the last chunk (which only the rows
+    of that chunk attend) against the oracle."""
+    from paper_2605_18753_amd.inputs import C5
+    w = C5
+    q, k, v = make_inputs(w, DEV)
+    d_o = torch.randn(q.shape, device=DEV, dtype=torch.float32).to(torch.bfloat16)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    dq, dk, dv = run_backward(w, q, k, v, run, d_o)
+    prm = U.oracle_params(w)
+    g, n, blk = w.g_q, w.n_q, w.block
+    t_all = B.list_stride(run.params)
+    rng = np.random.default_rng(1)
+    checked = skipped = 0
+    worst = 0.0
+    for b, r in ((0, 0), (3, 15), (1, 7)):
+        kn, vn = U.to_np(k[b, r]).astype(np.float64), U.to_np(v[b, r]).astype(np.float64)
+        kbar = orc.block_mean_summaries(kn, blk)
+        sl = slice(r * g, (r + 1) * g)
+        rows = sorted(set(rng.integers(0, n, 10).tolist()) | set(range(n - blk, n)))
+        dk_ref, dv_ref, dkb = np.zeros_like(kn), np.zeros_like(vn), np.zeros_like(kbar)
+        tail_ok = True
+        for i in rows:
+            qh = U.to_np(q[b, sl, i]).astype(np.float64)
+            doh = U.to_np(d_o[b, sl, i]).astype(np.float64)
+            rr = orc.dash_row_at(qh, kn, vn, kbar, prm, i)
+            bits = U.mask_bits(run.lists.mask[b, r, i].cpu().numpy(), t_all)
+            same = set(np.nonzero(bits[:rr.n_cand])[0].tolist()) == set(rr.routed.tolist())
+            scr_k, scr_v, scr_b = (dk_ref, dv_ref, dkb) if i >= n - blk else (np.zeros_like(kn), np.zeros_like(vn),
+                                                                              np.zeros_like(kbar))
+            ref_dq, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, scr_k, scr_v, scr_b)
+            hi, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, np.zeros_like(kn), np.zeros_like(vn),
+                                        np.zeros_like(kbar), margin_shift=1e-6)
+            if not same:
+                skipped += 1
+                tail_ok = tail_ok and i < n - blk
+                continue
+            got = U.to_np(dq[b, sl, i]).astype(np.float64)
+            allow = 6.0 * np.abs(hi - ref_dq)
+            worst = max(worst, rowwise_check(f"dq[{b},{r},{i}]", got, ref_dq, allow))
+            checked += 1
+        if tail_ok:
+            # keys of the last (complete) chunk: no later row routes to it, so these sums are complete
+            last = slice(n - blk, n)
+            for nm, got, ref in (("dk", dk, dk_ref), ("dv", dv, dv_ref)):
+                e = rowwise_check(f"{nm}[{b},{r},last chunk]", U.to_np(got[b, r, last]).astype(np.float64), ref[last],
+                                  np.zeros_like(ref[last]))
+                worst = max(worst, e)
+    assert checked >= 150 and skipped <= 6, (checked, skipped)
+    print(f"benchmark shape: {checked} rows checked, {skipped} skipped (support at the band), worst {worst:.2e}")
