@@ -566,12 +566,13 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
   char* v_t = lds + C::TILE_BYTES;             // and values
   char* q_t = lds + 2 * C::TILE_BYTES;         // 64 query rows of the current step
   char* d_t = lds + 3 * C::TILE_BYTES;         // and their dO rows
-  float* lse_s = reinterpret_cast<float*>(lds + 4 * C::TILE_BYTES);   // [64] per-row scalars
-  float* dsum_s = lse_s + 64;
-  float* bias_s = dsum_s + 64;
-  float* dx_s = bias_s + 64;
+  float* cmb_s = reinterpret_cast<float*>(lds + 4 * C::TILE_BYTES);   // [64] per-row scalars
+  float* dsum_s = cmb_s + 64;
+  float* dx_s = dsum_s + 64;
   int* pos_s = reinterpret_cast<int*>(dx_s + 64);
-  float* red = reinterpret_cast<float*>(pos_s + 64);                  // [4][D] dkbar partials
+  float* redf = reinterpret_cast<float*>(pos_s + 64);                 // [D] dkbar of the chunk
+  float* red = redf + D;                                              // [RG][D] dkbar partials
+  constexpr int RG = 256 / C::NCH, RPG = 64 / RG;   // dkbar: row groups per workgroup, rows per group
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -621,7 +622,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
   f32x16 dkacc[C::NDT], dvacc[C::NDT];
 #pragma unroll
   for (int t = 0; t < C::NDT; t++) { dkacc[t] = zero16(); dvacc[t] = zero16(); }
-  float kb0 = 0.f, kb1 = 0.f;      // dkbar partial of this thread's d pair over its 16 rows per step
+  float kbv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // dkbar partial: 8 d of this thread's rows
 
   // Steps: the 64-row halves of the row tiles whose bit is set in this chunk's column
   // mask, ascending.  The per-row scalars of a step (mask bit, bias, dx, log-sum-exp,
@@ -677,9 +678,9 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
           const int cdiag = f_tok / a.block;
           const bool isdiag = a.causal && c == cdiag;
           const int n_cand = a.causal ? max(cdiag - a.window, 0) : a.t_c;
-          bias_s[s_row] = bit ? (isdiag ? 0.f : f_bias * kLog2e) : -INFINITY;
+          // bias - log-sum-exp in base-2 units (-inf: the row does not attend the chunk)
+          cmb_s[s_row] = bit ? (isdiag ? 0.f : f_bias * kLog2e) - f_lse : -INFINITY;
           dx_s[s_row] = (bit && c < n_cand) ? f_dx : 0.f;
-          lse_s[s_row] = f_lse;
           dsum_s[s_row] = f_dsum;
           pos_s[s_row] = a.causal ? f_tok : 0x7fffffff;
           have = bit ? 1 : 0;
@@ -721,11 +722,11 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; q4++) {
           const int row0 = rh * 32 + 8 * q4 + 4 * h;
-          const float4 l4 = *reinterpret_cast<const float4*>(lse_s + row0);
           const float4 d4 = *reinterpret_cast<const float4*>(dsum_s + row0);
-          const float4 b4 = *reinterpret_cast<const float4*>(bias_s + row0);
-          const int4 p4 = *reinterpret_cast<const int4*>(pos_s + row0);
-          const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds[4] = {d4.x, d4.y, d4.z, d4.w};
+          const float4 b4 = *reinterpret_cast<const float4*>(cmb_s + row0);
+          int4 p4 = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+          if (masked) p4 = *reinterpret_cast<const int4*>(pos_s + row0);
+          const float ds[4] = {d4.x, d4.y, d4.z, d4.w};
           const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
           const int ps[4] = {p4.x, p4.y, p4.z, p4.w};
           float pv[4], dv[4];
@@ -733,7 +734,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
           for (int i = 0; i < 4; i++) {
             const int j = q4 * 4 + i;
             const bool dead = masked && (my_key > ps[i] || my_key >= a.n_kv);
-            const float p = dead ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bs[i] - ls[i]));
+            const float p = dead ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bs[i]));
             pv[i] = p;
             dv[i] = p * (dp[j] - ds[i]);
           }
@@ -752,15 +753,16 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
             dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(q_t, tl, th, g, t),
                                                                __builtin_bit_cast(bf16x8, pd[g]), dkacc[t], 0, 0, 0);
           }
-        // dkbar += sum_rows dx q: thread (wave, lane) takes d = 2 lane, 2 lane + 1 and rows 16 wave ..
-        if (any_cand && 2 * lane < D) {
-#pragma unroll 2
-          for (int rr = 0; rr < 16; rr++) {
-            const int row = wave * 16 + rr;
+        // dkbar += sum_rows dx q: thread tid takes the 8 d of chunk tid % NCH and the RPG rows of group tid / NCH
+        if (any_cand) {
+          const int cs = tid % C::NCH, rg = tid / C::NCH;
+#pragma unroll
+          for (int rr = 0; rr < RPG; rr++) {
+            const int row = rg * RPG + rr;
             const float dx = dx_s[row];
-            const uint32_t w = *reinterpret_cast<const uint32_t*>(q_t + tile_off<D>(row, 2 * lane));
-            kb0 = fmaf(dx, bf16_lo(w), kb0);
-            kb1 = fmaf(dx, bf16_hi(w), kb1);
+            const bf16x8 qv = *reinterpret_cast<const bf16x8*>(q_t + tile_off<D>(row, 8 * cs));
+#pragma unroll
+            for (int e = 0; e < 8; e++) kbv[e] = fmaf(dx, (float)qv[e], kbv[e]);
           }
         }
       }
@@ -770,7 +772,11 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
   // ---- combine the two row halves and write ------------------------------------
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a workgroup without any step: its K / V copies
   __syncthreads();
-  if (2 * lane < D) { red[wave * D + 2 * lane] = kb0; red[wave * D + 2 * lane + 1] = kb1; }
+  {
+    const int cs = tid % C::NCH, rg = tid / C::NCH;
+#pragma unroll
+    for (int e = 0; e < 8; e++) red[rg * D + 8 * cs + e] = kbv[e];
+  }
   float* xch = reinterpret_cast<float*>(lds);          // [2 kh][2 tensors][NDT*16][64 lanes]
   if (rh == 1) {
 #pragma unroll
@@ -780,6 +786,12 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
         xch[((kh * 2 + 0) * C::NDT * 16 + t * 16 + j) * 64 + lane] = dkacc[t][j];
         xch[((kh * 2 + 1) * C::NDT * 16 + t * 16 + j) * 64 + lane] = dvacc[t][j];
       }
+  }
+  __syncthreads();
+  if (tid < D) {
+    float t = 0.f;
+    for (int g = 0; g < RG; g++) t += red[g * D + tid];
+    redf[tid] = t;
   }
   __syncthreads();
   if (rh == 0 && my_key < a.n_kv) {
@@ -795,7 +807,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; i++) {
           const int j = q4 * 4 + i;
-          const float kbar_g = red[d0 + i] + red[D + d0 + i] + red[2 * D + d0 + i] + red[3 * D + d0 + i];
+          const float kbar_g = redf[d0 + i];
           kv[i] = (dkacc[t][j] + xch[((kh * 2 + 0) * C::NDT * 16 + t * 16 + j) * 64 + lane]) * a.scale +
                   kbar_g * kscale;
           vv[i] = dvacc[t][j] + xch[((kh * 2 + 1) * C::NDT * 16 + t * 16 + j) * 64 + lane];
@@ -863,7 +875,8 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
   {
     const size_t xch = (size_t)2 * 2 * C::NDT * 16 * 64 * 4;
     const size_t tiles = 4 * C::TILE_BYTES;
-    const size_t lds = (xch > tiles ? xch : tiles) + 5 * 64 * 4 + 4 * D * 4;
+    // tiles (reused for the end-of-kernel exchange), 4 per-row scalar arrays, dkbar and its partials
+    const size_t lds = (xch > tiles ? xch : tiles) + 4 * 64 * 4 + D * 4 + (size_t)(256 / C::NCH) * D * 4;
     auto kern = bwd_kv_kernel<D>;
     if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
       return e;
