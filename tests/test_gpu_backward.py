@@ -57,6 +57,9 @@ CASES = [
     ("window1", 1, 4, 2, 512, 128, 64, {"window": 1, "offset_sigma": 0.8}),
     ("noncausal", 1, 4, 2, 512, 128, 64, {"causal": False, "offset_sigma": 0.8}),
     ("one_chunk", 1, 4, 2, 50, 128, 64, {}),
+    ("sparse_gamma3", 1, 4, 2, 512, 128, 64, {"gamma": 3.0, "offset_sigma": 1.0}),
+    ("strong_prior_sigma03", 1, 4, 2, 512, 128, 64, {"sigma": 0.3, "offset_sigma": 0.8}),
+    ("mha_d64_b64", 1, 2, 2, 320, 64, 64, {"offset_sigma": 0.8}),
 ]
 
 
