@@ -33,12 +33,20 @@ chunks and z over the always-attended local tokens):
   summaries      block mean: dK_j += dkbar_c / B for every key j of chunk c
                  (the rounding of the summary cache to fp32 is treated as the identity)
 
+  learned summary  kbar_c = a^T K_c with a = softmax(K_c qbar scale) (Eq. 3): for a given
+                 dkbar_c,  da = K_c dkbar_c,  ds = a * (da - <a, da>),
+                 dK_c += a dkbar_c^T + scale ds qbar^T,  dqbar_c = scale K_c^T ds
+                 (local_attention_summaries_backward; the gradient of the trainable
+                 Stage 0 the paper refers to at the end of Sec. 3.3)
+
 Pins (tests/test_oracle_backward.py, CPU): central finite differences of the
 forward oracle's own outputs on tiny inputs with sparse supports (q, k, v, all
 alpha modes, GQA, window, non-causal); the entmax Jacobian against finite
 differences of entmax; the gamma -> 0 limit against a library's automatic
 differentiation of causal softmax attention; sum_c dx_{h,c} = 0 (shift
-invariance of entmax); zero gradient for keys and values no query attends.
+invariance of entmax); zero gradient for keys and values no query attends;
+the learned-summary backward against finite differences of
+local_attention_summaries and, at a zero query, against the block-mean rule.
 """
 from __future__ import annotations
 
@@ -159,3 +167,32 @@ def dash_backward_group(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.nda
         for c in range(dkbar.shape[0]):
             dk[c * blk:(c + 1) * blk] += dkbar[c] / float(blk)
     return dq, dk, dv, dkbar
+
+
+def local_attention_summaries_backward(k: np.ndarray, qbar: np.ndarray, block: int, dkbar: np.ndarray,
+                                       scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """Backward of dash_oracle.local_attention_summaries for one kv-head:
+    k [n, d], qbar [d] (one query for all chunks) or [T_c, d] (one per chunk),
+    dkbar [T_c, d].  Returns (dk [n, d], dqbar_c [T_c, d]): the gradient of the
+    keys through their chunk's summary and the gradient of the summary query
+    per chunk (a shared query's gradient is their sum).  The fp32 rounding of
+    the summaries is treated as the identity."""
+    k = np.asarray(k, dtype=np.float64)
+    n, d = k.shape
+    t_c = n // block
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    qb = np.broadcast_to(np.asarray(qbar, dtype=np.float64), (t_c, d))
+    dk = np.zeros_like(k)
+    dq = np.zeros((t_c, d))
+    for c in range(t_c):
+        keys = k[c * block:(c + 1) * block]
+        s = keys @ qb[c] * scale
+        e = np.exp(s - s.max())
+        a = e / e.sum()
+        g = np.asarray(dkbar[c], dtype=np.float64)
+        da = keys @ g
+        ds = a * (da - a @ da)
+        dk[c * block:(c + 1) * block] = np.outer(a, g) + scale * np.outer(ds, qb[c])
+        dq[c] = scale * (keys.T @ ds)
+    return dk, dq

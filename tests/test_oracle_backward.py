@@ -212,3 +212,56 @@ def test_no_candidates_means_plain_causal_gradients():
     (o[0] * torch.tensor(d_o)).sum().backward()
     for got, ref in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
         assert np.allclose(got, ref.numpy(), rtol=0, atol=1e-12 * max(1.0, np.abs(ref.numpy()).max()))
+
+
+@pytest.mark.parametrize("per_chunk", [False, True])
+def test_learned_summary_backward_against_finite_differences(per_chunk):
+    rng = np.random.default_rng(12)
+    n, d, block = 45, 8, 8                    # 5 complete chunks and a tail
+    t_c = n // block
+    k = rng.standard_normal((n, d))
+    qbar = rng.standard_normal((t_c, d) if per_chunk else d) * 2.0
+    G = rng.standard_normal((t_c, d))
+
+    def smooth(kk, qq):                        # the summaries without their fp32 rounding
+        out = np.empty((t_c, d))
+        qb = np.broadcast_to(qq, (t_c, d))
+        for c in range(t_c):
+            keys = kk[c * block:(c + 1) * block]
+            out[c] = scipy_softmax(keys @ qb[c] / math.sqrt(d)) @ keys
+        return out
+
+    from scipy.special import softmax as scipy_softmax
+    # the smooth form is the oracle's forward up to the rounding of its result
+    assert np.allclose(smooth(k, qbar), orc.local_attention_summaries(k[None], qbar, block)[0], rtol=0, atol=1e-6)
+    dk, dq = bwd.local_attention_summaries_backward(k, qbar, block, G)
+    assert np.all(dk[t_c * block:] == 0.0)     # the incomplete chunk has no summary
+    h = 1e-6
+    for _ in range(40):
+        i, j = int(rng.integers(0, t_c * block)), int(rng.integers(0, d))
+        kp, km = k.copy(), k.copy()
+        kp[i, j] += h
+        km[i, j] -= h
+        fd = ((smooth(kp, qbar) - smooth(km, qbar)) * G).sum() / (2 * h)
+        assert abs(fd - dk[i, j]) <= 1e-7 * max(1.0, np.abs(dk).max())
+    dq_total = dq if per_chunk else dq.sum(axis=0)
+    for idx in np.ndindex(*np.shape(qbar)):
+        qp, qm = np.array(qbar, dtype=np.float64), np.array(qbar, dtype=np.float64)
+        qp[idx] += h
+        qm[idx] -= h
+        fd = ((smooth(k, qp) - smooth(k, qm)) * G).sum() / (2 * h)
+        assert abs(fd - dq_total[idx]) <= 1e-7 * max(1.0, np.abs(dq_total).max())
+
+
+def test_learned_summary_backward_at_a_zero_query_is_the_block_mean_rule():
+    rng = np.random.default_rng(13)
+    n, d, block = 32, 8, 8
+    k = rng.standard_normal((n, d))
+    G = rng.standard_normal((n // block, d))
+    dk, dq = bwd.local_attention_summaries_backward(k, np.zeros(d), block, G)
+    assert np.allclose(dk, np.repeat(G / block, block, axis=0), rtol=1e-14, atol=0)
+    # and the query's gradient is the covariance-like term scale * K^T (a * (da - mean da))
+    for c in range(n // block):
+        keys = k[c * block:(c + 1) * block]
+        da = keys @ G[c]
+        assert np.allclose(dq[c], keys.T @ ((da - da.mean()) / block) / math.sqrt(d), rtol=1e-12, atol=1e-15)
