@@ -156,8 +156,13 @@ def bench_backward(w, steps, warmup, torch, B, make_inputs):
     st = prefill_stats(w, lists, torch)
     t_f = timed(lambda: B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws), steps, warmup, torch)
     t_b = timed(lambda: B.dash_attn_backward(p, q, k, v, d_o, kbar, lists, dq, dk, dv, wsb), steps, warmup, torch)
-    res = dict(ms_forward=t_f, ms_backward=t_b, **st)
-    del q, k, v, o, d_o, dq, dk, dv, ws, wsb, lists, kbar
+    # the learned Stage 0's own backward (summary gradient -> keys and summary query), timed alone
+    qbar = torch.randn((w.h_kv, w.head_dim), dtype=torch.float32, device=dev)
+    dkbar = torch.randn(B.kbar_shape(p), dtype=torch.float32, device=dev)
+    dqbar = torch.empty_like(dkbar)
+    t_sb = timed(lambda: B.dash_kbar_summarize_backward(p, k, qbar, dkbar, dk, dqbar), steps, 1, torch)
+    res = dict(ms_forward=t_f, ms_backward=t_b, ms_summarize_backward=t_sb, **st)
+    del q, k, v, o, d_o, dq, dk, dv, ws, wsb, lists, kbar, qbar, dkbar, dqbar
     torch.cuda.empty_cache()
     return res
 
@@ -422,6 +427,7 @@ def main():
             "backward": None if bwd is None else {
                 "workload": wb.name, "ms_forward": bwd["ms_forward"], "ms_backward": bwd["ms_backward"],
                 "backward_over_forward": bwd["ms_backward"] / bwd["ms_forward"],
+                "ms_learned_stage0_backward": bwd["ms_summarize_backward"],
                 "chunk_sparsity": bwd["sparsity"],
                 "backward_alg_tflops": tf(2.5 * bwd["f_alg"], bwd["ms_backward"]),
                 "backward_alg_mfma_frac": tf(2.5 * bwd["f_alg"], bwd["ms_backward"]) / MFMA_BF16_PEAK_TFLOPS,

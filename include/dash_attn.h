@@ -210,20 +210,42 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
  *   kbar           in  the block-mean summaries the forward wrote (fp32)
  *   mask, blk_bias, tau  in  the forward's Stage-1 outputs (all three required)
  *   dq, dk, dv     out gradients in the run dtype with the strides of q, k, v;
- *                  dk includes the path through the routing scores into the block
- *                  means (each key of a complete chunk receives 1/B of the
- *                  chunk summary's gradient); every element is written
+ *                  every element is written
+ *   dkbar          out, optional, fp32 [batch,h_kv,T_c,d] contiguous.  NULL: the
+ *                  summaries are block means and dk includes the path through the
+ *                  routing scores into them (each key of a complete chunk receives
+ *                  1/B of its summary's gradient).  Otherwise the summaries are an
+ *                  input of their own (e.g. from dash_kbar_summarize): their
+ *                  gradient is written here and dk holds the attention part only;
+ *                  dash_kbar_summarize_backward then carries it on to the keys and
+ *                  the summary query
  *   workspace      device scratch of dash_attn_backward_workspace_bytes bytes,
  *                  256-byte aligned (separate from, or reusing, the forward's)
- * bf16, n_q == n_kv and block-mean summaries only (DASH_EUNSUPPORTED otherwise,
- * also when a (batch, kv-head) slice of a tensor spans 2 GiB or more);
+ * bf16 and n_q == n_kv only (DASH_EUNSUPPORTED otherwise, also when a
+ * (batch, kv-head) slice of a tensor spans 2 GiB or more);
  * DASH_EINVAL for a NULL pointer. */
 int dash_attn_backward_workspace_bytes(const dash_params* p, size_t* out_bytes);
 int dash_attn_backward(const dash_params* p, const void* q, const void* k, const void* v,
                        const void* d_o, const float* kbar,
                        const uint32_t* mask, const float* blk_bias, const float* tau,
-                       void* dq, void* dk, void* dv,
+                       void* dq, void* dk, void* dv, float* dkbar,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of dash_kbar_summarize (Eq. 3; the trainable Stage 0 of Sec. 3.3's last
+ * paragraph): with a = softmax(K_c qbar scale) per chunk and the summaries'
+ * gradient dkbar, adds a dkbar_c^T + scale ds qbar^T (ds = a (K_c dkbar_c - <a, K_c dkbar_c>))
+ * to the keys' gradient and writes the summary query's gradient per chunk.
+ *   k, qbar, qbar_stride  in   as for dash_kbar_summarize
+ *   dkbar   in      fp32 [batch,h_kv,T_c,d] (dash_attn_backward's dkbar output)
+ *   dk      in/out  run dtype, strides of k: rows of complete chunks are read,
+ *                   incremented and written back
+ *   dqbar   out     fp32 [batch,h_kv,T_c,d]: the gradient of the query of every
+ *                   chunk; a query shared by several chunks (stride 0) has their sum
+ *                   as its gradient, which is left to the caller
+ * Errors as for dash_kbar_summarize. */
+int dash_kbar_summarize_backward(const dash_params* p, const void* k, const float* qbar,
+                                 const int64_t* qbar_stride, const float* dkbar, void* dk,
+                                 float* dqbar, void* stream);
 
 /* Static, NUL-terminated description of a dash_status. */
 const char* dash_strerror(int code);

@@ -55,7 +55,8 @@ _SIGNATURES = {
                                                ctypes.c_size_t, _V]),
     "dense_attn": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_attn_backward_workspace_bytes": (ctypes.c_int, [_P, ctypes.POINTER(ctypes.c_size_t)]),
-    "dash_attn_backward": (ctypes.c_int, [_P] + [_V] * 12 + [ctypes.c_size_t, _V]),
+    "dash_attn_backward": (ctypes.c_int, [_P] + [_V] * 13 + [ctypes.c_size_t, _V]),
+    "dash_kbar_summarize_backward": (ctypes.c_int, [_P, _V, _V, ctypes.POINTER(ctypes.c_int64), _V, _V, _V, _V]),
     "dash_strerror": (ctypes.c_char_p, [ctypes.c_int]),
 }
 
@@ -166,10 +167,7 @@ def dash_kbar_compress(p: dash_params, k: torch.Tensor, kbar: torch.Tensor,
                                              _stream()), "dash_kbar_compress")
 
 
-def dash_kbar_summarize(p: dash_params, k: torch.Tensor, qbar: torch.Tensor, kbar: torch.Tensor,
-                        first_chunk: int = 0, n_chunks: int = -1) -> None:
-    """qbar: fp32 tensor [h_kv, d] (one summary query per kv-head), [h_kv, T_c, d]
-    or [batch, h_kv, T_c, d] (one per chunk); only the strides are passed on."""
+def _qbar_strides(qbar: torch.Tensor):
     assert qbar.dtype == torch.float32 and qbar.stride(-1) == 1
     if qbar.dim() == 2:
         st = (0, qbar.stride(0), 0)
@@ -177,7 +175,14 @@ def dash_kbar_summarize(p: dash_params, k: torch.Tensor, qbar: torch.Tensor, kba
         st = (0, qbar.stride(0), qbar.stride(1))
     else:
         st = (qbar.stride(0), qbar.stride(1), qbar.stride(2))
-    arr = (ctypes.c_int64 * 3)(*st)
+    return (ctypes.c_int64 * 3)(*st)
+
+
+def dash_kbar_summarize(p: dash_params, k: torch.Tensor, qbar: torch.Tensor, kbar: torch.Tensor,
+                        first_chunk: int = 0, n_chunks: int = -1) -> None:
+    """qbar: fp32 tensor [h_kv, d] (one summary query per kv-head), [h_kv, T_c, d]
+    or [batch, h_kv, T_c, d] (one per chunk); only the strides are passed on."""
+    arr = _qbar_strides(qbar)
     _check(load_library().dash_kbar_summarize(ctypes.byref(p), _ptr(k), _ptr(qbar), arr, _ptr(kbar),
                                               first_chunk, n_chunks, _stream()), "dash_kbar_summarize")
 
@@ -240,13 +245,26 @@ def alloc_backward_workspace(p: dash_params, device) -> torch.Tensor:
     return torch.empty(backward_workspace_bytes(p) + 256, dtype=torch.uint8, device=device)
 
 
-def dash_attn_backward(p, q, k, v, d_o, kbar, lists: Lists, dq, dk, dv, ws: torch.Tensor) -> None:
-    """Backward of dash_attn_prefill; lists.mask / bias / tau are the forward's outputs."""
+def dash_attn_backward(p, q, k, v, d_o, kbar, lists: Lists, dq, dk, dv, ws: torch.Tensor, dkbar=None) -> None:
+    """Backward of dash_attn_prefill; lists.mask / bias / tau are the forward's outputs.
+    dkbar None: block-mean summaries (their gradient is folded into dk)."""
     wp, wn = _ws_ptr(ws)
+    if dkbar is not None:
+        assert dkbar.dtype == torch.float32 and dkbar.is_contiguous() and tuple(dkbar.shape) == kbar_shape(p)
     _check(load_library().dash_attn_backward(ctypes.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(d_o),
                                              _ptr(kbar), _ptr(lists.mask), _ptr(lists.bias), _ptr(lists.tau),
-                                             _ptr(dq), _ptr(dk), _ptr(dv), wp, wn, _stream()),
+                                             _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dkbar), wp, wn, _stream()),
            "dash_attn_backward")
+
+
+def dash_kbar_summarize_backward(p, k, qbar: torch.Tensor, dkbar: torch.Tensor, dk, dqbar: torch.Tensor) -> None:
+    """Backward of dash_kbar_summarize; qbar as there ([h_kv,d], [h_kv,T_c,d] or [batch,h_kv,T_c,d])."""
+    strides = _qbar_strides(qbar)
+    assert dkbar.dtype == torch.float32 and dkbar.is_contiguous() and tuple(dkbar.shape) == kbar_shape(p)
+    assert dqbar.dtype == torch.float32 and dqbar.is_contiguous() and tuple(dqbar.shape) == kbar_shape(p)
+    _check(load_library().dash_kbar_summarize_backward(ctypes.byref(p), _ptr(k), _ptr(qbar), strides, _ptr(dkbar),
+                                                       _ptr(dk), _ptr(dqbar), _stream()),
+           "dash_kbar_summarize_backward")
 
 
 def kbar_shape(p: dash_params):

@@ -283,7 +283,7 @@ int dash_attn_backward_workspace_bytes(const dash_params* p, size_t* out_bytes) 
 
 int dash_attn_backward(const dash_params* p, const void* q, const void* k, const void* v,
                        const void* d_o, const float* kbar, const uint32_t* mask, const float* blk_bias,
-                       const float* tau, void* dq, void* dk, void* dv, void* workspace,
+                       const float* tau, void* dq, void* dk, void* dv, float* dkbar, void* workspace,
                        size_t workspace_bytes, void* stream) {
   Layout L;
   const int rc = backward_layout(p, &L);
@@ -293,8 +293,23 @@ int dash_attn_backward(const dash_params* p, const void* q, const void* k, const
     return DASH_EINVAL;
   if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < backward_workspace_bytes(*p, L))
     return DASH_EWORKSPACE;
-  return launch_backward(*p, L, q, k, v, d_o, kbar, mask, blk_bias, tau, dq, dk, dv, (char*)workspace,
+  return launch_backward(*p, L, q, k, v, d_o, kbar, mask, blk_bias, tau, dq, dk, dv, dkbar, (char*)workspace,
                          (hipStream_t)stream) == hipSuccess ? DASH_OK : DASH_ELAUNCH;
+}
+
+int dash_kbar_summarize_backward(const dash_params* p, const void* k, const float* qbar,
+                                 const int64_t* qbar_stride, const float* dkbar, void* dk, float* dqbar,
+                                 void* stream) {
+  Layout L;
+  int rc = make_layout(p, &L);
+  if (rc != DASH_OK) return rc;
+  if (!k || !qbar || !qbar_stride || !dk || ((!dkbar || !dqbar) && L.t_c > 0)) return DASH_EINVAL;
+  const int vec = p->dtype == DASH_BF16 ? 8 : 4;
+  for (int i = 0; i < 3; i++)
+    if (qbar_stride[i] < 0 || qbar_stride[i] % vec != 0) return DASH_EINVAL;
+  if (((uintptr_t)qbar & 15) != 0) return DASH_EINVAL;
+  return launch_kbar_summarize_bwd(*p, L, k, qbar, qbar_stride, dkbar, dk, dqbar, (hipStream_t)stream) == hipSuccess
+             ? DASH_OK : DASH_ELAUNCH;
 }
 
 const char* dash_strerror(int code) {

@@ -48,6 +48,7 @@ struct BwdArgs {
   float* dxd;              // [batch, h_q, n_q, t_all]: entmax-score gradient by chunk id
   float* dq32;             // [batch, h_q, n_q, D]: attention part of dq
   uint32_t* colmask;       // [batch*h_kv, t_all, cwords]: bit T set iff row tile T attends the chunk
+  float* dkbar_out;        // optional [batch, h_kv, t_c, D]: gradient of the summaries (then not folded into dk)
   int h_q, h_kv, g_q, n_q, n_kv, block, t_c, t_all, words, causal, window, n_tiles, hb, cwords;
   int64_t qs_b, qs_h, qs_t, ks_b, ks_h, ks_t, vs_b, vs_h, vs_t, os_b, os_h, os_t;
   float c1, scale, xscale, pexp, sigma;
@@ -794,8 +795,11 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
     redf[tid] = t;
   }
   __syncthreads();
+  if (a.dkbar_out && tid < D && c < a.t_c && kpos0 % a.block == 0)
+    a.dkbar_out[(((int64_t)b * a.h_kv + r) * a.t_c + c) * D + tid] = redf[tid] * a.xscale;
   if (rh == 0 && my_key < a.n_kv) {
-    const float kscale = c < a.t_c ? a.xscale / (float)a.block : 0.f;
+    // block-mean summaries: every key of a complete chunk receives 1/B of the chunk's dkbar
+    const float kscale = (c < a.t_c && !a.dkbar_out) ? a.xscale / (float)a.block : 0.f;
     uint16_t* dkp = a.dk + b * a.ks_b + r * a.ks_h + (int64_t)my_key * a.ks_t;
     uint16_t* dvp = a.dv + b * a.vs_b + r * a.vs_h + (int64_t)my_key * a.vs_t;
 #pragma unroll
@@ -889,9 +893,10 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
 
 hipError_t launch_backward(const dash_params& p, const Layout& L, const void* q, const void* k, const void* v,
                            const void* d_o, const float* kbar, const uint32_t* mask,
-                           const float* bias, const float* tau, void* dq, void* dk, void* dv, char* ws,
-                           hipStream_t st) {
+                           const float* bias, const float* tau, void* dq, void* dk, void* dv, float* dkbar_out,
+                           char* ws, hipStream_t st) {
   BwdArgs a;
+  a.dkbar_out = dkbar_out;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.d_o = (const uint16_t*)d_o;
   a.dq = (uint16_t*)dq; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;

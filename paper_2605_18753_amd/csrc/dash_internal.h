@@ -57,8 +57,11 @@ hipError_t launch_s2_f32(const dash_params& p, const Layout& L, const void* q, c
 size_t backward_workspace_bytes(const dash_params& p, const Layout& L);
 hipError_t launch_backward(const dash_params& p, const Layout& L, const void* q, const void* k, const void* v,
                            const void* d_o, const float* kbar, const uint32_t* mask,
-                           const float* bias, const float* tau, void* dq, void* dk, void* dv, char* ws,
-                           hipStream_t st);
+                           const float* bias, const float* tau, void* dq, void* dk, void* dv, float* dkbar_out,
+                           char* ws, hipStream_t st);
+hipError_t launch_kbar_summarize_bwd(const dash_params& p, const Layout& L, const void* k, const float* qbar,
+                                     const int64_t* qs, const float* dkbar, void* dk, float* dqbar,
+                                     hipStream_t st);
 hipError_t launch_decode_s2(const dash_params& p, const Layout& L, const void* q, const void* k,
                             const void* v, void* o, const uint32_t* mask, const float* bias,
                             float* partials, bool dense, hipStream_t st);

@@ -198,3 +198,60 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows():
                 worst = max(worst, e)
     assert checked >= 150 and skipped <= 6, (checked, skipped)
     print(f"benchmark shape: {checked} rows checked, {skipped} skipped (support at the band), worst {worst:.2e}")
+
+
+@pytest.mark.parametrize("per_chunk", [False, True], ids=["query_per_head", "query_per_chunk"])
+def test_backward_through_learned_summaries(per_chunk):
+    """The trainable Stage 0: forward with dash_kbar_summarize, backward with the
+    summaries as an input of their own (dkbar output), then
+    dash_kbar_summarize_backward down to the keys and the summary query."""
+    w = Workload("bwd_learned", 1, 4, 2, 512, 512, 128, 64, seed=29, offset_sigma=0.8)
+    q, k, v = gen(w)
+    t_c = w.n_kv // w.block
+    gq = torch.Generator().manual_seed(3)
+    qbar = (torch.randn((w.h_kv, t_c, w.head_dim) if per_chunk else (w.h_kv, w.head_dim), generator=gq) * 0.7).to(DEV)
+    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(7)).to(torch.bfloat16).to(DEV)
+    run = U.run_prefill_learned(w, q, k, v, qbar)
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q, k, v))
+    dkbar = torch.full_like(run.kbar, float("nan"))
+    dqbar = torch.full_like(run.kbar, float("nan"))
+    ws = B.alloc_backward_workspace(run.params, DEV)
+    B.dash_attn_backward(run.params, q, k, v, d_o, run.kbar, run.lists, dq, dk, dv, ws, dkbar=dkbar)
+    B.dash_kbar_summarize_backward(run.params, k, qbar, dkbar, dk, dqbar)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv, dkbar, dqbar):
+        assert torch.isfinite(t.float()).all()
+
+    prm = U.oracle_params(w)
+    g, n, blk = w.g_q, w.n_q, w.block
+    qn, kn, vn, don = (U.to_np(t).astype(np.float64) for t in (q, k, v, d_o))
+    qbn = U.to_np(qbar).astype(np.float64)
+    t_all = B.list_stride(run.params)
+    for r in range(w.h_kv):
+        kbar_ref = orc.local_attention_summaries(kn[0, r][None], qbn[r], blk)[0]
+        for i in range(n):
+            rr = orc.dash_row_at(qn[0, r * g:(r + 1) * g, i], kn[0, r], vn[0, r], kbar_ref, prm, i)
+            bits = U.mask_bits(run.lists.mask[0, r, i].cpu().numpy(), t_all)
+            assert set(np.nonzero(bits[:rr.n_cand])[0].tolist()) == set(rr.routed.tolist()), "choose another seed"
+        sl = slice(r * g, (r + 1) * g)
+        outs = []
+        for shift in (0.0, 1e-6, -1e-6):
+            rq, rk, rv, rkb = bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm, kbar=kbar_ref,
+                                                      margin_shift=shift)
+            sk, sq = bwd.local_attention_summaries_backward(kn[0, r], qbn[r], blk, rkb)
+            outs.append((rq, rk + sk, rv, rkb, sq))
+        ref = outs[0]
+        allow = [3.0 * (np.abs(outs[1][j] - ref[j]) + np.abs(outs[2][j] - ref[j])) for j in range(5)]
+        got = (U.to_np(dq[0, sl]), U.to_np(dk[0, r]), U.to_np(dv[0, r]), U.to_np(dkbar[0, r]), U.to_np(dqbar[0, r]))
+        worst = {}
+        for j, nm in enumerate(("dq", "dk", "dv", "dkbar", "dqbar")):
+            worst[nm] = rowwise_check(f"learned {nm}[{r}]", got[j].astype(np.float64), ref[j], allow[j])
+        if not per_chunk:
+            # one query per kv-head: its gradient is the sum over the chunks
+            tot_ref, tot_got = ref[4].sum(axis=0), got[4].astype(np.float64).sum(axis=0)
+            assert np.abs(tot_got - tot_ref).max() <= 2e-2 * np.abs(tot_ref).max() + allow[4].sum(axis=0).max()
+        # the summary path must be a visible part of dk
+        share = np.abs(outs[0][1] - bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm,
+                                                            kbar=kbar_ref)[1]).max() / np.abs(ref[1]).max()
+        assert share > 0.02, share
+        print(f"learned summaries, kv-head {r}: " + " ".join(f"{a} {b:.2e}" for a, b in worst.items()))

@@ -128,8 +128,8 @@ def test_backward_argument_errors():
     p = params()
     need = B.backward_workspace_bytes(p)
     assert need > 2 * 8 * 1024 * 4 + 8 * 1024 * 128 * 4
-    ptrs = [256] * 11
-    for i in range(11):
+    ptrs = [256] * 12          # q k v d_o kbar mask bias tau dq dk dv dkbar
+    for i in range(11):          # the last one (dkbar) is optional
         bad = list(ptrs)
         bad[i] = None
         assert lib.dash_attn_backward(ctypes.byref(p), *bad, 256, need, None) == -1, i
@@ -147,6 +147,20 @@ def test_backward_argument_errors():
     far = params()
     far.q_stride[1] = 1 << 31                                       # heads 4 GiB apart: 32-bit offsets do not reach
     assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(far), ctypes.byref(n)) == -2
+
+
+def test_summarize_backward_argument_errors():
+    lib = B.load_library()
+    p = params()
+    ok = (ctypes.c_int64 * 3)(0, 128, 0)
+    good = [256, 256, ok, 256, 256, 256]         # k qbar strides dkbar dk dqbar
+    for i in range(6):
+        bad = list(good)
+        bad[i] = None
+        assert lib.dash_kbar_summarize_backward(ctypes.byref(p), *bad, None) == -1, i
+    assert lib.dash_kbar_summarize_backward(ctypes.byref(p), 256, 264, ok, 256, 256, 256, None) == -1   # alignment
+    assert lib.dash_kbar_summarize_backward(ctypes.byref(p), 256, 256, (ctypes.c_int64 * 3)(0, 100, 0), 256, 256,
+                                            256, None) == -1
 
 
 def test_strerror():
