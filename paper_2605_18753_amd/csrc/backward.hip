@@ -670,102 +670,98 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
   int tok0 = next_step();
   if (tok0 >= 0 && lane < 16) fetch(tok0);
   while (tok0 >= 0) {
-    {
-      {
-        __syncthreads();                    // the previous step is no longer read
-        int have = 0;
-        if (lane < 16) {
-          const bool bit = f_ok && ((f_mask >> (c & 31)) & 1u);
-          const int cdiag = f_tok / a.block;
-          const bool isdiag = a.causal && c == cdiag;
-          const int n_cand = a.causal ? max(cdiag - a.window, 0) : a.t_c;
-          // bias - log-sum-exp in base-2 units (-inf: the row does not attend the chunk)
-          cmb_s[s_row] = bit ? (isdiag ? 0.f : f_bias * kLog2e) - f_lse : -INFINITY;
-          dx_s[s_row] = (bit && c < n_cand) ? f_dx : 0.f;
-          dsum_s[s_row] = f_dsum;
-          pos_s[s_row] = a.causal ? f_tok : 0x7fffffff;
-          have = bit ? 1 : 0;
-        }
-        const int cur_tok0 = tok0;
-        tok0 = next_step();
-        if (tok0 >= 0 && lane < 16) fetch(tok0);
-        if (!__syncthreads_or(have)) continue;
-        // is the chunk a routing candidate of any row of this step?  (the candidate count
-        // grows with the position, so the step's last token decides)
-        const bool any_cand = c < (a.causal ? max(min(cur_tok0 + tok_step - 1, a.n_q - 1) / a.block - a.window, 0)
-                                            : a.t_c);
-        // the key mask matters only where the rows' own chunk is this one, or at the end of the sequence
-        const bool masked = (a.causal && (cur_tok0 + tok_step - 1) / a.block >= c && cur_tok0 / a.block <= c) ||
-                            kpos0 + 64 > a.n_kv;
-        const uint32_t soff_q = (uint32_t)cur_tok0 * (uint32_t)a.qs_t * 2u;
-        const uint32_t soff_o = (uint32_t)cur_tok0 * (uint32_t)a.os_t * 2u;
+    __syncthreads();                    // the previous step is no longer read
+    int have = 0;
+    if (lane < 16) {
+      const bool bit = f_ok && ((f_mask >> (c & 31)) & 1u);
+      const int cdiag = f_tok / a.block;
+      const bool isdiag = a.causal && c == cdiag;
+      const int n_cand = a.causal ? max(cdiag - a.window, 0) : a.t_c;
+      // bias - log-sum-exp in base-2 units (-inf: the row does not attend the chunk)
+      cmb_s[s_row] = bit ? (isdiag ? 0.f : f_bias * kLog2e) - f_lse : -INFINITY;
+      dx_s[s_row] = (bit && c < n_cand) ? f_dx : 0.f;
+      dsum_s[s_row] = f_dsum;
+      pos_s[s_row] = a.causal ? f_tok : 0x7fffffff;
+      have = bit ? 1 : 0;
+    }
+    const int cur_tok0 = tok0;
+    tok0 = next_step();
+    if (tok0 >= 0 && lane < 16) fetch(tok0);
+    if (!__syncthreads_or(have)) continue;
+    // is the chunk a routing candidate of any row of this step?  (the candidate count
+    // grows with the position, so the step's last token decides)
+    const bool any_cand = c < (a.causal ? max(min(cur_tok0 + tok_step - 1, a.n_q - 1) / a.block - a.window, 0)
+                                        : a.t_c);
+    // the key mask matters only where the rows' own chunk is this one, or at the end of the sequence
+    const bool masked = (a.causal && (cur_tok0 + tok_step - 1) / a.block >= c && cur_tok0 / a.block <= c) ||
+                        kpos0 + 64 > a.n_kv;
+    const uint32_t soff_q = (uint32_t)cur_tok0 * (uint32_t)a.qs_t * 2u;
+    const uint32_t soff_o = (uint32_t)cur_tok0 * (uint32_t)a.os_t * 2u;
 #pragma unroll
-        for (int i = 0; i < C::COPIES; i++) {
-          const uint32_t la = lds0 + 2 * C::TILE_BYTES + wave * 1024 + i * 4096;
-          copy16_to_lds(q_rs, la, q_off, soff_q + i * q_step);
-          copy16_to_lds(o_rs, la + C::TILE_BYTES, o_off, soff_o + i * o_step);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+    for (int i = 0; i < C::COPIES; i++) {
+      const uint32_t la = lds0 + 2 * C::TILE_BYTES + wave * 1024 + i * 4096;
+      copy16_to_lds(q_rs, la, q_off, soff_q + i * q_step);
+      copy16_to_lds(o_rs, la + C::TILE_BYTES, o_off, soff_o + i * o_step);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 
-        // S = Q K^T and dP = dO V^T for this wave's 32 rows x 32 keys
-        // (the base offsets are made opaque here so that the per-slice offsets derived from
-        // them are formed next to their use instead of being kept in registers across steps)
-        uint32_t a_b = a_rd, b_b = b_rd, tl = t_lo, th = t_hi;
-        asm volatile("" : "+v"(a_b), "+v"(b_b), "+v"(tl), "+v"(th));
-        f32x16 s = zero16(), dp = zero16();
+    // S = Q K^T and dP = dO V^T for this wave's 32 rows x 32 keys
+    // (the base offsets are made opaque here so that the per-slice offsets derived from
+    // them are formed next to their use instead of being kept in registers across steps)
+    uint32_t a_b = a_rd, b_b = b_rd, tl = t_lo, th = t_hi;
+    asm volatile("" : "+v"(a_b), "+v"(b_b), "+v"(tl), "+v"(th));
+    f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ks++) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(q_t, a_b, 2 * ks), read_a<D>(k_t, b_b, 2 * ks), s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(d_t, a_b, 2 * ks), read_a<D>(v_t, b_b, 2 * ks), dp, 0, 0, 0);
-        }
-        u32x4 pp[2], pd[2];
+    for (int ks = 0; ks < D / 16; ks++) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(q_t, a_b, 2 * ks), read_a<D>(k_t, b_b, 2 * ks), s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(d_t, a_b, 2 * ks), read_a<D>(v_t, b_b, 2 * ks), dp, 0, 0, 0);
+    }
+    u32x4 pp[2], pd[2];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          const int row0 = rh * 32 + 8 * q4 + 4 * h;
-          const float4 d4 = *reinterpret_cast<const float4*>(dsum_s + row0);
-          const float4 b4 = *reinterpret_cast<const float4*>(cmb_s + row0);
-          int4 p4 = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
-          if (masked) p4 = *reinterpret_cast<const int4*>(pos_s + row0);
-          const float ds[4] = {d4.x, d4.y, d4.z, d4.w};
-          const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
-          const int ps[4] = {p4.x, p4.y, p4.z, p4.w};
-          float pv[4], dv[4];
+    for (int q4 = 0; q4 < 4; q4++) {
+      const int row0 = rh * 32 + 8 * q4 + 4 * h;
+      const float4 d4 = *reinterpret_cast<const float4*>(dsum_s + row0);
+      const float4 b4 = *reinterpret_cast<const float4*>(cmb_s + row0);
+      int4 p4 = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+      if (masked) p4 = *reinterpret_cast<const int4*>(pos_s + row0);
+      const float ds[4] = {d4.x, d4.y, d4.z, d4.w};
+      const float bs[4] = {b4.x, b4.y, b4.z, b4.w};
+      const int ps[4] = {p4.x, p4.y, p4.z, p4.w};
+      float pv[4], dv[4];
 #pragma unroll
-          for (int i = 0; i < 4; i++) {
-            const int j = q4 * 4 + i;
-            const bool dead = masked && (my_key > ps[i] || my_key >= a.n_kv);
-            const float p = dead ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bs[i]));
-            pv[i] = p;
-            dv[i] = p * (dp[j] - ds[i]);
-          }
-          pp[q4 >> 1][(q4 & 1) * 2 + 0] = cvt_bf16x2(pv[0], pv[1]);
-          pp[q4 >> 1][(q4 & 1) * 2 + 1] = cvt_bf16x2(pv[2], pv[3]);
-          pd[q4 >> 1][(q4 & 1) * 2 + 0] = cvt_bf16x2(dv[0], dv[1]);
-          pd[q4 >> 1][(q4 & 1) * 2 + 1] = cvt_bf16x2(dv[2], dv[3]);
-        }
-        // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over this wave's 32 rows)
+      for (int i = 0; i < 4; i++) {
+        const int j = q4 * 4 + i;
+        const bool dead = masked && (my_key > ps[i] || my_key >= a.n_kv);
+        const float p = dead ? 0.f : __builtin_amdgcn_exp2f(fmaf(s[j], a.c1, bs[i]));
+        pv[i] = p;
+        dv[i] = p * (dp[j] - ds[i]);
+      }
+      pp[q4 >> 1][(q4 & 1) * 2 + 0] = cvt_bf16x2(pv[0], pv[1]);
+      pp[q4 >> 1][(q4 & 1) * 2 + 1] = cvt_bf16x2(pv[2], pv[3]);
+      pd[q4 >> 1][(q4 & 1) * 2 + 0] = cvt_bf16x2(dv[0], dv[1]);
+      pd[q4 >> 1][(q4 & 1) * 2 + 1] = cvt_bf16x2(dv[2], dv[3]);
+    }
+    // dV^T += dO^T P,  dK^T += Q^T dS  (contraction over this wave's 32 rows)
 #pragma unroll
-        for (int g = 0; g < 2; g++)
+    for (int g = 0; g < 2; g++)
 #pragma unroll
-          for (int t = 0; t < C::NDT; t++) {
-            dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(d_t, tl, th, g, t),
-                                                               __builtin_bit_cast(bf16x8, pp[g]), dvacc[t], 0, 0, 0);
-            dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(q_t, tl, th, g, t),
-                                                               __builtin_bit_cast(bf16x8, pd[g]), dkacc[t], 0, 0, 0);
-          }
-        // dkbar += sum_rows dx q: thread tid takes the 8 d of chunk tid % NCH and the RPG rows of group tid / NCH
-        if (any_cand) {
-          const int cs = tid % C::NCH, rg = tid / C::NCH;
+      for (int t = 0; t < C::NDT; t++) {
+        dvacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(d_t, tl, th, g, t),
+                                                           __builtin_bit_cast(bf16x8, pp[g]), dvacc[t], 0, 0, 0);
+        dkacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t<D>(q_t, tl, th, g, t),
+                                                           __builtin_bit_cast(bf16x8, pd[g]), dkacc[t], 0, 0, 0);
+      }
+    // dkbar += sum_rows dx q: thread tid takes the 8 d of chunk tid % NCH and the RPG rows of group tid / NCH
+    if (any_cand) {
+      const int cs = tid % C::NCH, rg = tid / C::NCH;
 #pragma unroll
-          for (int rr = 0; rr < RPG; rr++) {
-            const int row = rg * RPG + rr;
-            const float dx = dx_s[row];
-            const bf16x8 qv = *reinterpret_cast<const bf16x8*>(q_t + tile_off<D>(row, 8 * cs));
+      for (int rr = 0; rr < RPG; rr++) {
+        const int row = rg * RPG + rr;
+        const float dx = dx_s[row];
+        const bf16x8 qv = *reinterpret_cast<const bf16x8*>(q_t + tile_off<D>(row, 8 * cs));
 #pragma unroll
-            for (int e = 0; e < 8; e++) kbv[e] = fmaf(dx, (float)qv[e], kbv[e]);
-          }
-        }
+        for (int e = 0; e < 8; e++) kbv[e] = fmaf(dx, (float)qv[e], kbv[e]);
       }
     }
   }
