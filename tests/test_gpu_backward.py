@@ -147,12 +147,13 @@ def test_backward_token_major_layout_and_workspace_reuse():
         assert torch.equal(got, want)
 
 
-def test_backward_at_the_benchmark_shape_on_sampled_rows():
-    """The training-shaped workload in the launch configuration bench.py times: dq of
-    sampled query rows and dk, dv of the keys of the last chunk (which only the rows
-    of that chunk attend) against the oracle."""
-    from paper_2605_18753_amd.inputs import C5
-    w = C5
+@pytest.mark.parametrize("which", ["C5", "C2"])
+def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
+    """The training-shaped workload in the launch configuration bench.py times (and the
+    32k GQA prefill shape): dq of sampled query rows and dk, dv of the keys of the last
+    chunk (which only the rows of that chunk attend) against the oracle."""
+    from paper_2605_18753_amd.inputs import NAMED
+    w = NAMED[which]
     q, k, v = make_inputs(w, DEV)
     d_o = torch.randn(q.shape, device=DEV, dtype=torch.float32).to(torch.bfloat16)
     run = U.run_prefill(w, q, k, v, want_idx=False)
@@ -163,7 +164,7 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows():
     rng = np.random.default_rng(1)
     checked = skipped = 0
     worst = 0.0
-    for b, r in ((0, 0), (3, 15), (1, 7)):
+    for b, r in ((0, 0), (w.batch - 1, w.h_kv - 1), (w.batch // 2, w.h_kv // 2)):
         kn, vn = U.to_np(k[b, r]).astype(np.float64), U.to_np(v[b, r]).astype(np.float64)
         kbar = orc.block_mean_summaries(kn, blk)
         sl = slice(r * g, (r + 1) * g)
