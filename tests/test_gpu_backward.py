@@ -42,7 +42,7 @@ def rowwise_check(name, got, ref, allow, tol=2e-2):
     assert not bad.any(), (f"{name}: {int(bad.sum())} elements off, worst excess "
                            f"{(err - bound).max():.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}, "
                            f"ref there {ref[np.unravel_index(np.argmax(err - bound), err.shape)]:.3e}")
-    return float((err / np.maximum(rowmax, floor)).max())
+    return float((err / np.maximum(np.maximum(rowmax, floor), 1e-300)).max())
 
 
 CASES = [
@@ -60,6 +60,10 @@ CASES = [
     ("sparse_gamma3", 1, 4, 2, 512, 128, 64, {"gamma": 3.0, "offset_sigma": 1.0}),
     ("strong_prior_sigma03", 1, 4, 2, 512, 128, 64, {"sigma": 0.3, "offset_sigma": 0.8}),
     ("mha_d64_b64", 1, 2, 2, 320, 64, 64, {"offset_sigma": 0.8}),
+    # degenerate lengths: a single token, exactly one chunk, one chunk plus one token
+    ("one_token", 2, 4, 2, 1, 128, 64, {}),
+    ("exactly_one_chunk", 1, 4, 2, 64, 128, 64, {}),
+    ("one_chunk_plus_one", 1, 4, 2, 65, 128, 64, {}),
 ]
 
 
