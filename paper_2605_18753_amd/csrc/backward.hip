@@ -447,10 +447,21 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
     // group then holds all scores; lane dp keeps the per-head results of the heads
     // hh = dp (mod 8) (slopes to memory, their sums in registers).
     constexpr int DP = D / 8;                      // d range of one lane
+    // With few heads the routing part of dq is accumulated in the same sweep:
+    // sum_c dx_c kbar_c = sum_c (g_c dw_hat_c) kbar_c - ratio sum_c g_c kbar_c, two sums whose
+    // weights are known chunk by chunk, so the summary rows are read once.
+    constexpr bool FUSE = 2 * G * DP <= 64;
     const int cs = lane >> 3, dp = lane & 7;
     float s0[G], s1[G];
 #pragma unroll
     for (int hh = 0; hh < G; hh++) s0[hh] = s1[hh] = 0.f;
+    float a1[FUSE ? G : 1][DP], a2[FUSE ? G : 1][DP];
+    if constexpr (FUSE) {
+#pragma unroll
+      for (int hh = 0; hh < G; hh++)
+#pragma unroll
+        for (int j = 0; j < DP; j++) a1[hh][j] = a2[hh][j] = 0.f;
+    }
     for (int e0 = 0; e0 < n_r; e0 += 8) {
       const int e = e0 + cs;
       const bool live = e < n_r;
@@ -459,9 +470,11 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
       float x[G];
 #pragma unroll
       for (int hh = 0; hh < G; hh++) x[hh] = 0.f;
+      float kvr[DP];
 #pragma unroll
       for (int d4 = 0; d4 < DP / 4; d4++) {
         const float4 kv = krow[d4];
+        kvr[4 * d4] = kv.x; kvr[4 * d4 + 1] = kv.y; kvr[4 * d4 + 2] = kv.z; kvr[4 * d4 + 3] = kv.w;
 #pragma unroll
         for (int hh = 0; hh < G; hh++) {
           const float4 qv = *reinterpret_cast<const float4*>(qs + hh * D + dp * DP + d4 * 4);
@@ -493,6 +506,17 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
             s1[hh] += gd[hh] * dwh;
             a.dxd[(((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c] = gd[hh];
           }
+        if constexpr (FUSE) {
+#pragma unroll
+          for (int hh = 0; hh < G; hh++) {
+            const float w1 = gd[hh] * dwh, w2 = gd[hh];
+#pragma unroll
+            for (int j = 0; j < DP; j++) {
+              a1[hh][j] = fmaf(w1, kvr[j], a1[hh][j]);
+              a2[hh][j] = fmaf(w2, kvr[j], a2[hh][j]);
+            }
+          }
+        }
       }
     }
     float ratio[G];
@@ -501,6 +525,42 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
       const float t0 = wave_sum(s0[hh]), t1 = wave_sum(s1[hh]);
       ratio[hh] = t0 > 0.f ? t1 / t0 : 0.f;
     }
+    if constexpr (FUSE) {
+      // dx for the key-owner kernel (each lane turns the slopes it wrote itself into dx)
+      for (int e0 = 0; e0 < n_r; e0 += 8) {
+        const int e = e0 + cs;
+        if (e < n_r) {
+          const int c = cidx[e];
+          const float dwh = dwl[e];
+#pragma unroll
+          for (int hh = 0; hh < G; hh++)
+            if ((hh & 7) == dp) {
+              float* px = a.dxd + (((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok) * a.t_all + c;
+              *px = *px * (dwh - ratio[hh]);
+            }
+        }
+      }
+      // routing part of dq: combine the two sums, add up the 8 chunk slots (lanes that differ
+      // in cs), and hand lane (cs, dp) the d = dp DP + cs DP/8 .. of its output pair
+#pragma unroll
+      for (int hh = 0; hh < G; hh++) {
+        float v0 = 0.f, v1 = 0.f;
+#pragma unroll
+        for (int j = 0; j < DP; j++) {
+          float t = a1[hh][j] - ratio[hh] * a2[hh][j];
+          t += __shfl_xor(t, 8);
+          t += __shfl_xor(t, 16);
+          t += __shfl_xor(t, 32);
+          if (D == 128) {
+            if ((j >> 1) == cs) { if (j & 1) v1 = t; else v0 = t; }
+          } else {
+            if (j == cs) v0 = t;
+          }
+        }
+        acc_q[hh][0] = v0;
+        acc_q[hh][1] = v1;
+      }
+    } else
     // sweep B, one segment of SEG routed chunks at a time: dx (each lane turns the slopes
     // it wrote itself into dx), then dq += dx kbar with the lanes over d
     for (int e0 = 0; e0 < n_r; e0 += SEG) {
@@ -541,17 +601,21 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
       }
     }
   }
-  // final dq = attention part + routing part
+  // final dq = attention part + routing part; a lane owns the d pair 2 lane .. (D = 128) or the
+  // single d = lane (D = 64) in the two-sweep variant, d = 16 dp + 2 cs .. or 8 dp + cs in the fused one
+  constexpr bool FUSED = 2 * G * (D / 8) <= 64;
+  const int d_own = FUSED ? (D == 128 ? 16 * (lane & 7) + 2 * (lane >> 3) : 8 * (lane & 7) + (lane >> 3))
+                          : (D == 128 ? 2 * lane : lane);
 #pragma unroll
   for (int hh = 0; hh < G; hh++) {
     const int64_t row = ((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok;
     uint16_t* out = a.dq + b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t;
     if (D == 128) {
-      const float2 base = *reinterpret_cast<const float2*>(a.dq32 + row * D + 2 * lane);
-      *reinterpret_cast<uint32_t*>(out + 2 * lane) =
+      const float2 base = *reinterpret_cast<const float2*>(a.dq32 + row * D + d_own);
+      *reinterpret_cast<uint32_t*>(out + d_own) =
           cvt_bf16x2(fmaf(a.xscale, acc_q[hh][0], base.x), fmaf(a.xscale, acc_q[hh][1], base.y));
     } else {
-      out[lane] = (uint16_t)f32_to_bf16_bits(fmaf(a.xscale, acc_q[hh][0], a.dq32[row * D + lane]));
+      out[d_own] = (uint16_t)f32_to_bf16_bits(fmaf(a.xscale, acc_q[hh][0], a.dq32[row * D + d_own]));
     }
   }
 }
