@@ -17,11 +17,12 @@
 //   dq_h += c sum_c dx_{h,c} kbar_c,  dkbar_c = c sum_{rows} dx q,  c = gamma (alpha-1) scale
 //   dK_j += dkbar_c / B for the keys of a complete chunk c (block mean).
 //
-// Three kernels:
+// Kernels:
 //   bwd_q_kernel   owns 128 (token, head) rows like the forward kernel and walks the
-//                  union of their chunks twice: first for the row log-sum-exp and D,
-//                  then for dq (attention part, fp32), dd and a dense copy of the
-//                  bias; it also marks, per chunk, which row tiles attend it.
+//                  union of their chunks; launched twice: <GRAD = false> for the row
+//                  log-sum-exp and D, <GRAD = true> for dq (attention part, fp32), dd
+//                  and a dense copy of the bias; the latter also marks, per chunk,
+//                  which row tiles attend it.
 //   bwd_route_kernel  one wave per (kv-head, token): prior and entmax Jacobian,
 //                  dx per head and chunk, the routing part of dq, final dq.
 //   bwd_kv_kernel  owns a 64-key tile, walks the row tiles that attend its chunk and
@@ -112,14 +113,17 @@ __global__ void bwd_fill_zero_kernel(uint32_t* p, size_t n) {
 // ---------------------------------------------------------------------------
 // Row-owner kernel.
 // ---------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
+// GRAD = false: the first walk (row log-sum-exp and D into the workspace; few registers, dO
+// fragments in registers, three workgroups per CU).  GRAD = true: the second walk (dq, bias
+// gradient, column masks; dO rows as an LDS operand, two workgroups per CU).
+template <int D, bool GRAD>
+__global__ __launch_bounds__(256, GRAD ? 2 : 3) void bwd_q_kernel(BwdArgs a) {
   using C = BCfg<D>;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   char* k_t = lds;                            // K tile
   char* v_t = lds + C::TILE_BYTES;            // V tile
-  char* do_t = lds + 2 * C::TILE_BYTES;       // dO rows of the workgroup's 128 rows (stationary)
-  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + 4 * C::TILE_BYTES);   // [64]
+  char* do_t = lds + 2 * C::TILE_BYTES;       // GRAD: dO rows of the workgroup's 128 rows (stationary)
+  uint32_t* wgmask = reinterpret_cast<uint32_t*>(lds + (GRAD ? 4 : 2) * C::TILE_BYTES);   // [64]
   uint32_t* wvmask = wgmask + 64;                                            // [4][64]
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -140,12 +144,19 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
   const int cw = (tok_w0 < a.n_q ? tok_w0 : a.n_q - 1) / a.block;
   const bool wave_ok = tok_w0 < a.n_q;
 
-  // ---- row fragments: q (registers) and dO (LDS, each wave its own 32 rows) as B operands
-  bf16x8 qf[D / 16];
+  // ---- row fragments as B operands: q in registers; dO in registers (first walk) or in LDS
+  // (second walk, each wave its own 32 rows)
+  bf16x8 qf[D / 16], dof[GRAD ? 1 : D / 16];
   {
     const uint16_t* qp = a.q + b * a.qs_b + my_head * a.qs_h + (int64_t)row_tok * a.qs_t + h * 8;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+  if constexpr (!GRAD) {
+    const uint16_t* dop = a.d_o + b * a.os_b + my_head * a.os_h + (int64_t)row_tok * a.os_t + h * 8;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ks++) dof[ks] = *reinterpret_cast<const bf16x8*>(dop + ks * 16);
+  } else {
     const u32x4 o_rs = make_rsrc(a.d_o + b * a.os_b + (int64_t)r * a.g_q * a.os_h,
                                  ((int64_t)(a.g_q - 1) * a.os_h + ((int64_t)a.n_q - 1) * a.os_t + D) * 2);
     constexpr int RPI = 64 / C::NCH;             // rows one copy instruction covers
@@ -183,6 +194,7 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
     }
   __syncthreads();
   // tell the key-owner kernel which chunks this row tile attends
+  if constexpr (GRAD)
   for (int wi = tid; wi < a.words; wi += 256) {
     uint32_t m = wgmask[wi];
     while (m) {
@@ -232,13 +244,18 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
   // D = <P, dP> = <dO, o> is taken from the latter two in fp32 (the stored bf16
   // output would put its rounding error into every dz of the row)
   float m_run = -INFINITY, l_run = 0.f, dn_run = 0.f, lse2 = 0.f, dsum = 0.f;
-  f32x16 dqacc[C::NDT];
+  f32x16 dqacc[GRAD ? C::NDT : 1];
 #pragma unroll
-  for (int t = 0; t < C::NDT; t++) dqacc[t] = zero16();
+  for (int t = 0; t < (GRAD ? C::NDT : 1); t++) dqacc[t] = zero16();
   float db_acc = 0.f;
+  if constexpr (GRAD) {
+    const int64_t row = ((int64_t)b * a.h_q + my_head) * a.n_q + row_tok;
+    lse2 = a.lse[row];
+    dsum = a.dsum[row];
+  }
 
-  for (int pass = 0; pass < 2; pass++) {
-    const bool grad = pass == 1;
+  {
+    constexpr bool grad = GRAD;
     it_wi = -1; it_sub = nsub - 1; it_u = -1; it_bits = 0u;
     trk_rank = 0; trk_wi = -1; trk_word = 0; trk_has = false;
     float trk_next = (trk_ok && a.t_all > 0) ? trk_bias[0] : 0.f;
@@ -293,8 +310,11 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
 #pragma unroll
         for (int ks = 0; ks < D / 16; ks++) {
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(k_t, a_rd, 2 * ks + kt), qf[ks], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(v_t, a_rd, 2 * ks + kt),
-                                                       read_a<D>(do_t, do_rd, 2 * ks), dp, 0, 0, 0);
+          if constexpr (GRAD)
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(v_t, a_rd, 2 * ks + kt),
+                                                         read_a<D>(do_t, do_rd, 2 * ks), dp, 0, 0, 0);
+          else
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_a<D>(v_t, a_rd, 2 * ks + kt), dof[ks], dp, 0, 0, 0);
         }
         // key mask: causal inside the diagonal chunk, and the end of the sequence
         if (diag || kpos0 + 64 > a.n_kv) {
@@ -339,7 +359,7 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
           }
         }
       }
-      if (!grad) continue;
+      if constexpr (GRAD) {
       db_acc += dssum;
       // dQ^T += K^T dS^T
 #pragma unroll
@@ -357,8 +377,9 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
         if (!diag && trk_ok && trk_has) a.dbd[trk_base * a.t_all + cu] = mine;
         db_acc = 0.f;
       }
+      }
     }
-    if (!grad) {
+    if constexpr (!GRAD) {
       const float l_tot = l_run + __shfl_xor(l_run, 32);
       const float dn_tot = dn_run + __shfl_xor(dn_run, 32);
       lse2 = (m_run == -INFINITY ? 0.f : m_run) + __builtin_amdgcn_logf(l_tot);   // v_log_f32: log2
@@ -369,8 +390,11 @@ __global__ __launch_bounds__(256, 2) void bwd_q_kernel(BwdArgs a) {
   // ---- outputs -----------------------------------------------------------------
   if (row_ok) {
     const int64_t row = ((int64_t)b * a.h_q + my_head) * a.n_q + my_tok;
-    if (h == 0) { a.lse[row] = lse2; a.dsum[row] = dsum; }
+    if constexpr (!GRAD) {
+      if (h == 0) { a.lse[row] = lse2; a.dsum[row] = dsum; }
+    }
     float* dq = a.dq32 + row * D;
+    if constexpr (GRAD)
 #pragma unroll
     for (int t = 0; t < C::NDT; t++)
 #pragma unroll
@@ -928,8 +952,16 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
+    const size_t lds = 2 * C::TILE_BYTES + 5 * 64 * 4;
+    auto kern = bwd_q_kernel<D, false>;
+    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+      return e;
+    hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
     const size_t lds = 4 * C::TILE_BYTES + 5 * 64 * 4;
-    auto kern = bwd_q_kernel<D>;
+    auto kern = bwd_q_kernel<D, true>;
     if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
       return e;
     hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
