@@ -18,6 +18,7 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, os.path.dirname(os.path.dirname(HERE)))
 from oracle import dash_oracle as orc  # noqa: E402
+from oracle import dash_oracle_bwd as bwd  # noqa: E402
 
 
 def entmax_cases():
@@ -60,6 +61,26 @@ def path_case():
     }
 
 
+def backward_case():
+    """The backward pass (end of Sec. 3.3; sparse entmax Jacobian) on the tiny problem of
+    path_case with a fixed upstream gradient: dq, dk, dv and the summaries' gradient of
+    each kv-head."""
+    rng = np.random.default_rng(20240607)
+    n, d = 16, 4
+    q = rng.standard_normal((1, 4, n, d)).round(3)
+    k = rng.standard_normal((1, 2, n, d)).round(3)
+    v = rng.standard_normal((1, 2, n, d)).round(3)
+    k[0, :, 8:12] += 1.5
+    d_o = np.random.default_rng(77).standard_normal((1, 4, n, d)).round(3)
+    prm = orc.DashParams(block=4, alpha=1.5, gamma=2.0, sigma=2.0, causal=True)
+    heads = []
+    for r in range(2):
+        dq, dk, dv, dkbar = bwd.dash_backward_group(q[0, 2 * r:2 * r + 2], k[0, r], v[0, r], d_o[0, 2 * r:2 * r + 2], prm)
+        heads.append({n_: [[repr(float(t)) for t in row] for row in a.reshape(-1, d)]
+                      for n_, a in (("dq", dq), ("dk", dk), ("dv", dv), ("dkbar", dkbar))})
+    return {"d_o": d_o.tolist(), "kv_heads": heads}
+
+
 def main():
     with open(os.path.join(HERE, "entmax_cases.json"), "w") as f:
         json.dump({"what": "alpha-entmax threshold and probabilities (Eq. 2; App. A), oracle-generated",
@@ -67,7 +88,10 @@ def main():
     with open(os.path.join(HERE, "tiny_path.json"), "w") as f:
         json.dump({"what": "DashAttention forward on a tiny causal GQA input (Alg. 1-3, Prop. 1), oracle-generated",
                    **path_case()}, f, indent=1)
-    print("wrote entmax_cases.json, tiny_path.json")
+    with open(os.path.join(HERE, "tiny_backward.json"), "w") as f:
+        json.dump({"what": "DashAttention backward on the input of tiny_path.json (end of Sec. 3.3), oracle-generated",
+                   **backward_case()}, f, indent=1)
+    print("wrote entmax_cases.json, tiny_path.json, tiny_backward.json")
 
 
 if __name__ == "__main__":

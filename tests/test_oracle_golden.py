@@ -7,6 +7,7 @@ import os
 import numpy as np
 
 from oracle import dash_oracle as orc
+from oracle import dash_oracle_bwd as bwd
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -36,3 +37,16 @@ def test_tiny_path_golden():
     assert [[int(c) for c in rr.routed] for rr in rows] == g["routed"]
     for rr in rows:
         assert list(rr.routed) == sorted(rr.routed) and all(0 <= c < rr.n_cand for c in rr.routed)
+
+
+def test_tiny_backward_golden():
+    g, gb = _load("tiny_path.json"), _load("tiny_backward.json")
+    q, k, v = (np.asarray(g[n], dtype=np.float64) for n in ("q", "k", "v"))
+    d_o = np.asarray(gb["d_o"], dtype=np.float64)
+    prm = orc.DashParams(**g["params"])
+    for r, want in enumerate(gb["kv_heads"]):
+        got = bwd.dash_backward_group(q[0, 2 * r:2 * r + 2], k[0, r], v[0, r], d_o[0, 2 * r:2 * r + 2], prm)
+        for name, arr in zip(("dq", "dk", "dv", "dkbar"), got):
+            ref = np.asarray([[float(t) for t in row] for row in want[name]])
+            assert np.allclose(arr.reshape(ref.shape), ref, rtol=0, atol=1e-12 * max(1.0, np.abs(ref).max())), name
+        assert np.abs(np.asarray([[float(t) for t in row] for row in want["dkbar"]])).max() > 0
