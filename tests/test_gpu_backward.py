@@ -151,10 +151,10 @@ def test_backward_token_major_layout_and_workspace_reuse():
         assert torch.equal(got, want)
 
 
-@pytest.mark.parametrize("which", ["C5", "C2"])
+@pytest.mark.parametrize("which", ["C5", "C2", "C4"])
 def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
     """The training-shaped workload in the launch configuration bench.py times (and the
-    32k GQA prefill shape): dq of sampled query rows and dk, dv of the keys of the last
+    32k GQA prefill and the 128k / chunk-128 shapes): dq of sampled query rows and dk, dv of the keys of the last
     chunk (which only the rows of that chunk attend) against the oracle."""
     from paper_2605_18753_amd.inputs import NAMED
     w = NAMED[which]
@@ -168,24 +168,27 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
     rng = np.random.default_rng(1)
     checked = skipped = 0
     worst = 0.0
-    for b, r in ((0, 0), (w.batch - 1, w.h_kv - 1), (w.batch // 2, w.h_kv // 2)):
+    # the 128k shape costs the oracle about 0.1 s per row: one kv-head and sampled rows only there
+    light = w.n_q > 65536
+    groups = ((0, 3),) if light else ((0, 0), (w.batch - 1, w.h_kv - 1), (w.batch // 2, w.h_kv // 2))
+    for b, r in groups:
         kn, vn = U.to_np(k[b, r]).astype(np.float64), U.to_np(v[b, r]).astype(np.float64)
         kbar = orc.block_mean_summaries(kn, blk)
         sl = slice(r * g, (r + 1) * g)
-        rows = sorted(set(rng.integers(0, n, 10).tolist()) | set(range(n - blk, n)))
+        rows = sorted(set(rng.integers(0, n, 24).tolist()) | set(range(n - 4, n))) if light else \
+            sorted(set(rng.integers(0, n, 10).tolist()) | set(range(n - blk, n)))
+        tail_ok = not light
         dk_ref, dv_ref, dkb = np.zeros_like(kn), np.zeros_like(vn), np.zeros_like(kbar)
-        tail_ok = True
+        scratch = (np.zeros_like(kn), np.zeros_like(vn), np.zeros_like(kbar))    # sums nobody reads
         for i in rows:
             qh = U.to_np(q[b, sl, i]).astype(np.float64)
             doh = U.to_np(d_o[b, sl, i]).astype(np.float64)
             rr = orc.dash_row_at(qh, kn, vn, kbar, prm, i)
             bits = U.mask_bits(run.lists.mask[b, r, i].cpu().numpy(), t_all)
             same = set(np.nonzero(bits[:rr.n_cand])[0].tolist()) == set(rr.routed.tolist())
-            scr_k, scr_v, scr_b = (dk_ref, dv_ref, dkb) if i >= n - blk else (np.zeros_like(kn), np.zeros_like(vn),
-                                                                              np.zeros_like(kbar))
+            scr_k, scr_v, scr_b = (dk_ref, dv_ref, dkb) if i >= n - blk else scratch
             ref_dq, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, scr_k, scr_v, scr_b)
-            hi, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, np.zeros_like(kn), np.zeros_like(vn),
-                                        np.zeros_like(kbar), margin_shift=1e-6)
+            hi, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, *scratch, margin_shift=1e-6)
             if not same:
                 skipped += 1
                 tail_ok = tail_ok and i < n - blk
@@ -201,7 +204,7 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
                 e = rowwise_check(f"{nm}[{b},{r},last chunk]", U.to_np(got[b, r, last]).astype(np.float64), ref[last],
                                   np.zeros_like(ref[last]))
                 worst = max(worst, e)
-    assert checked >= 150 and skipped <= 6, (checked, skipped)
+    assert checked >= (20 if light else 150) and skipped <= 6, (checked, skipped)
     print(f"benchmark shape: {checked} rows checked, {skipped} skipped (support at the band), worst {worst:.2e}")
 
 
