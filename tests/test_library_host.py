@@ -168,3 +168,13 @@ def test_strerror():
     assert lib.dash_strerror(0) == b"ok"
     for c in (-1, -2, -3, -4, 17):
         assert len(lib.dash_strerror(c)) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more must end with a message, before anything touches a GPU."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
