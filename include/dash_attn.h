@@ -207,7 +207,8 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
  *   d_o            in  gradient of the loss with respect to the forward's output o,
  *                  layout and strides of o (o itself is not needed: <dO, o> is
  *                  recomputed in fp32)
- *   kbar           in  the block-mean summaries the forward wrote (fp32)
+ *   kbar           in  the summaries Stage 1 routed on (fp32): the block means the
+ *                  forward wrote, or the learned ones of dash_kbar_summarize
  *   mask, blk_bias, tau  in  the forward's Stage-1 outputs (all three required)
  *   dq, dk, dv     out gradients in the run dtype with the strides of q, k, v;
  *                  every element is written
@@ -220,7 +221,8 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
  *                  dash_kbar_summarize_backward then carries it on to the keys and
  *                  the summary query
  *   workspace      device scratch of dash_attn_backward_workspace_bytes bytes,
- *                  256-byte aligned (separate from, or reusing, the forward's)
+ *                  256-byte aligned (separate from, or reusing, the forward's; two
+ *                  calls in flight must not share it)
  * bf16 and n_q == n_kv only (DASH_EUNSUPPORTED otherwise, also when a
  * (batch, kv-head) slice of a tensor spans 2 GiB or more);
  * DASH_EINVAL for a NULL pointer. */
