@@ -223,6 +223,9 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
  *   workspace      device scratch of dash_attn_backward_workspace_bytes bytes,
  *                  256-byte aligned (separate from, or reusing, the forward's; two
  *                  calls in flight must not share it)
+ * For alpha > 2 the entmax slope is unbounded at the edge of the support, so rows
+ * with a chunk close to its threshold have gradients only as accurate as the fp32
+ * scores allow (checked against the oracle up to alpha = 3).
  * bf16 and n_q == n_kv only (DASH_EUNSUPPORTED otherwise, also when a
  * (batch, kv-head) slice of a tensor spans 2 GiB or more);
  * DASH_EINVAL for a NULL pointer. */
