@@ -240,9 +240,10 @@ __global__ __launch_bounds__(256, GRAD ? 2 : 3) void bwd_q_kernel(BwdArgs a) {
   const uint32_t t_lo = tile_off<D>(4 * h + (s16 >> 2), 16 * a16 + 4 * (s16 & 3));
   const uint32_t t_hi = tile_off<D>(8 + 4 * h + (s16 >> 2), 16 * a16 + 4 * (s16 & 3));
 
-  // first pass: running max, sum of exponentials and sum of exponentials times dP;
-  // D = <P, dP> = <dO, o> is taken from the latter two in fp32 (the stored bf16
-  // output would put its rounding error into every dz of the row)
+  // first walk (GRAD = false): running max, sum of exponentials and sum of exponentials
+  // times dP; D = <P, dP> = <dO, o> is taken from the latter two in fp32 (the stored bf16
+  // output would put its rounding error into every dz of the row).  Second walk: both
+  // come from the workspace.
   float m_run = -INFINITY, l_run = 0.f, dn_run = 0.f, lse2 = 0.f, dsum = 0.f;
   f32x16 dqacc[GRAD ? C::NDT : 1];
 #pragma unroll
@@ -256,8 +257,6 @@ __global__ __launch_bounds__(256, GRAD ? 2 : 3) void bwd_q_kernel(BwdArgs a) {
 
   {
     constexpr bool grad = GRAD;
-    it_wi = -1; it_sub = nsub - 1; it_u = -1; it_bits = 0u;
-    trk_rank = 0; trk_wi = -1; trk_word = 0; trk_has = false;
     float trk_next = (trk_ok && a.t_all > 0) ? trk_bias[0] : 0.f;
     float bias_row = 0.f;
     bool wave_on = false, diag = false;
