@@ -924,9 +924,7 @@ size_t backward_workspace_bytes(const dash_params& p, const Layout& L) {
 
 template <int D, int G> static hipError_t launch_route(const BwdArgs& a, int batch, hipStream_t st) {
   const size_t lds = (size_t)G * D * 4 + (size_t)a.t_c * 8 + (size_t)G * 64 * 4 + 64;
-  auto kern = bwd_route_kernel<D, G>;
-  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
+  auto kern = bwd_route_kernel<D, G>;        // at most 29 KB of LDS (t_c <= 2048): no opt-in needed
   hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)batch * a.h_kv * a.n_q)), dim3(64), lds, st, a);
   return hipGetLastError();
 }
@@ -941,8 +939,18 @@ template <int D> static hipError_t launch_route_g(const BwdArgs& a, int batch, h
   }
 }
 
+// more than 64 KB of dynamic LDS needs an opt-in, once per kernel (not a stream operation, so it
+// is done on the first call only and a later call can be captured into a graph)
+static hipError_t allow_lds(const void* kern, size_t bytes, bool& done) {
+  if (done) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  done = e == hipSuccess;
+  return e;
+}
+
 template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hipStream_t st) {
   using C = BCfg<D>;
+  static bool done_lse = false, done_grad = false, done_kv = false;
   hipError_t e;
   {
     const size_t nwords = (size_t)a.hb * a.t_all * a.cwords;
@@ -953,16 +961,14 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
   {
     const size_t lds = 2 * C::TILE_BYTES + 5 * 64 * 4;
     auto kern = bwd_q_kernel<D, false>;
-    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
-      return e;
+    if ((e = allow_lds((const void*)kern, lds, done_lse)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
     const size_t lds = 4 * C::TILE_BYTES + 5 * 64 * 4;
     auto kern = bwd_q_kernel<D, true>;
-    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
-      return e;
+    if ((e = allow_lds((const void*)kern, lds, done_grad)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
@@ -973,8 +979,7 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
     // tiles (reused for the end-of-kernel exchange), 4 per-row scalar arrays, dkbar and its partials
     const size_t lds = (xch > tiles ? xch : tiles) + 4 * 64 * 4 + D * 4 + (size_t)(256 / C::NCH) * D * 4;
     auto kern = bwd_kv_kernel<D>;
-    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
-      return e;
+    if ((e = allow_lds((const void*)kern, lds, done_kv)) != hipSuccess) return e;
     const int ktiles = (a.n_kv + 63) / 64;
     hipLaunchKernelGGL(kern, dim3(ktiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;

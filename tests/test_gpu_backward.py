@@ -272,3 +272,48 @@ def test_backward_through_learned_summaries(per_chunk):
                                                             kbar=kbar_ref)[1]).max() / np.abs(ref[1]).max()
         assert share > 0.02, share
         print(f"learned summaries, kv-head {r}: " + " ".join(f"{a} {b:.2e}" for a, b in worst.items()))
+
+
+def test_forward_and_backward_replay_from_a_captured_graph():
+    """Neither call allocates, synchronises or clears memory with a memset node, so a
+    training step can be captured once and replayed: three replays with new inputs in
+    the same buffers, eager work in between, each equal to the eager results."""
+    w = Workload("train_graph", 2, 8, 2, 700, 700, 128, 64, seed=19, offset_sigma=0.8)
+    q, k, v = gen(w)
+    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(2)).to(torch.bfloat16).to(DEV)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
+    lists = B.Lists.allocate(p, DEV)
+    ws, wsb = B.alloc_workspace(p, DEV), B.alloc_backward_workspace(p, DEV)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+
+    def step():
+        B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws)
+        B.dash_attn_backward(p, q, k, v, d_o, kbar, lists, dq, dk, dv, wsb)
+
+    step()                                                     # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    gen_x = torch.Generator(device=DEV).manual_seed(5)
+    for rep in range(3):
+        for t in (q, d_o):
+            t.copy_(torch.randn(t.shape, generator=gen_x, device=DEV).to(t.dtype))
+        for t in (o, dq, dk, dv):
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (o, dq, dk, dv)]
+        for t in (o, dq, dk, dv):
+            t.zero_()
+        step()                                                 # eager, same inputs
+        torch.cuda.synchronize()
+        for a_, b_ in zip(got, (o, dq, dk, dv)):
+            assert torch.equal(a_, b_), rep
+        assert dq.float().abs().max() > 0 and torch.isfinite(dk.float()).all()
