@@ -226,8 +226,10 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
  * For alpha > 2 the entmax slope is unbounded at the edge of the support, so rows
  * with a chunk close to its threshold have gradients only as accurate as the fp32
  * scores allow (checked against the oracle up to alpha = 3).
- * bf16 and n_q == n_kv only (DASH_EUNSUPPORTED otherwise, also when a
- * (batch, kv-head) slice of a tensor spans 2 GiB or more);
+ * n_q == n_kv only (DASH_EUNSUPPORTED otherwise, also when a (batch, kv-head)
+ * slice of a bf16 tensor spans 2 GiB or more).  bf16 tensors take the matrix-core
+ * kernels; fp32 tensors take plain fp32 kernels that accumulate dk and dv with
+ * atomics (a correctness vehicle like the fp32 forward, sums in no fixed order);
  * DASH_EINVAL for a NULL pointer. */
 int dash_attn_backward_workspace_bytes(const dash_params* p, size_t* out_bytes);
 int dash_attn_backward(const dash_params* p, const void* q, const void* k, const void* v,

@@ -261,8 +261,9 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
 static int backward_layout(const dash_params* p, Layout* L) {
   int rc = make_layout(p, L);
   if (rc != DASH_OK) return rc;
-  if (p->dtype != DASH_BF16 || p->n_q != p->n_kv) return DASH_EUNSUPPORTED;
-  // the kernels address a (batch, kv-head) slice of every tensor with 32-bit byte offsets
+  if (p->n_q != p->n_kv) return DASH_EUNSUPPORTED;
+  if (p->dtype == DASH_F32) return DASH_OK;      // plain pointers with 64-bit offsets
+  // the bf16 kernels address a (batch, kv-head) slice of every tensor with 32-bit byte offsets
   const int64_t lim = (int64_t)1 << 31;
   const int64_t g = L->g_q, n = p->n_q, d = p->head_dim;
   if (((g - 1) * p->q_stride[1] + (n - 1) * p->q_stride[2] + d) * 2 >= lim ||

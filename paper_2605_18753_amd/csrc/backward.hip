@@ -417,7 +417,7 @@ __device__ __forceinline__ void pow_and_slope(float u, float p, float& w, float&
   else { w = __builtin_amdgcn_exp2f(p * __builtin_amdgcn_logf(u)); g = p * w / u; }
 }
 
-template <int D, int G>
+template <int D, int G, typename T>
 __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
   constexpr int SEG = 64;
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -438,7 +438,7 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
 
   for (int i = lane; i < G * D; i += 64) {
     const int hh = i / D, d = i % D;
-    qs[i] = bf16_bits_to_f32(a.q[b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t + d]);
+    qs[i] = elem<T>::ld(reinterpret_cast<const T*>(a.q) + b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t + d);
   }
   // routed candidates, ascending
   int n_r = 0;
@@ -632,13 +632,14 @@ __global__ __launch_bounds__(64) void bwd_route_kernel(BwdArgs a) {
 #pragma unroll
   for (int hh = 0; hh < G; hh++) {
     const int64_t row = ((int64_t)b * a.h_q + r * G + hh) * a.n_q + tok;
-    uint16_t* out = a.dq + b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t;
+    T* out = reinterpret_cast<T*>(a.dq) + b * a.qs_b + (r * G + hh) * a.qs_h + (int64_t)tok * a.qs_t;
     if (D == 128) {
       const float2 base = *reinterpret_cast<const float2*>(a.dq32 + row * D + d_own);
-      *reinterpret_cast<uint32_t*>(out + d_own) =
-          cvt_bf16x2(fmaf(a.xscale, acc_q[hh][0], base.x), fmaf(a.xscale, acc_q[hh][1], base.y));
+      const float v0 = fmaf(a.xscale, acc_q[hh][0], base.x), v1 = fmaf(a.xscale, acc_q[hh][1], base.y);
+      if constexpr (sizeof(T) == 2) *reinterpret_cast<uint32_t*>(out + d_own) = cvt_bf16x2(v0, v1);
+      else *reinterpret_cast<float2*>(out + d_own) = make_float2(v0, v1);
     } else {
-      out[d_own] = (uint16_t)f32_to_bf16_bits(fmaf(a.xscale, acc_q[hh][0], a.dq32[row * D + d_own]));
+      elem<T>::st(out + d_own, fmaf(a.xscale, acc_q[hh][0], a.dq32[row * D + d_own]));
     }
   }
 }
@@ -909,6 +910,181 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// fp32 tensors: plain VALU kernels (the correctness vehicle of the fp32
+// configuration, like the fp32 forward; not a tuned path).  One workgroup per
+// (token, kv-head), one wave per query head, lanes over the 64 keys of a tile
+// for the logits and over the head dimension for the sums; dK, dV and the bias
+// gradient are accumulated with fp32 atomics into zeroed outputs.  The routing
+// kernel above is shared with the bf16 path.
+// ---------------------------------------------------------------------------
+__global__ void bwd_f32_zero_kernel(BwdArgs a, int d, int batch) {
+  const int64_t rows = (int64_t)batch * a.h_kv * a.n_kv;
+  float* dk = reinterpret_cast<float*>(a.dk);
+  float* dv = reinterpret_cast<float*>(a.dv);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < rows * d; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = i / d;
+    const int e = (int)(i % d);
+    const int key = (int)(row % a.n_kv);
+    const int64_t hb = row / a.n_kv;
+    const int r = (int)(hb % a.h_kv), b = (int)(hb / a.h_kv);
+    dk[b * a.ks_b + r * a.ks_h + (int64_t)key * a.ks_t + e] = 0.f;
+    dv[b * a.vs_b + r * a.vs_h + (int64_t)key * a.vs_t + e] = 0.f;
+  }
+}
+
+__global__ __launch_bounds__(256) void bwd_f32_row_kernel(BwdArgs a, int d) {
+  __shared__ float qs[4][128], dos[4][128], ps[4][64], zs[4][64];
+  const int tok = blockIdx.x, r = blockIdx.y, b = blockIdx.z;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int pos = tok;                                   // n_q == n_kv
+  const int cw = pos / a.block;
+  const int nsub = a.block >> 6;
+  const int64_t base = ((int64_t)b * a.h_kv + r) * a.n_q + tok;
+  const uint32_t* mrow = a.mask + base * a.words;
+  const float* brow = a.bias + base * a.t_all;
+  const float* kb = reinterpret_cast<const float*>(a.k) + b * a.ks_b + r * a.ks_h;
+  const float* vb = reinterpret_cast<const float*>(a.v) + b * a.vs_b + r * a.vs_h;
+  float* dkb = reinterpret_cast<float*>(a.dk) + b * a.ks_b + r * a.ks_h;
+  float* dvb = reinterpret_cast<float*>(a.dv) + b * a.vs_b + r * a.vs_h;
+
+  for (int hl = wave; hl < a.g_q; hl += 4) {
+    const int head = r * a.g_q + hl;
+    const float* qp = reinterpret_cast<const float*>(a.q) + b * a.qs_b + head * a.qs_h + (int64_t)tok * a.qs_t;
+    const float* dop = reinterpret_cast<const float*>(a.d_o) + b * a.os_b + head * a.os_h + (int64_t)tok * a.os_t;
+    for (int e = lane; e < d; e += 64) { qs[wave][e] = qp[e]; dos[wave][e] = dop[e]; }
+    __builtin_amdgcn_wave_barrier();
+    // logit and dP = <dO, v> of this lane's key of a 64-key tile
+    auto key_terms = [&](int kpos0, bool diag, float bias, float& z, float& dp) -> bool {
+      const int key = kpos0 + lane;
+      const bool valid = key < a.n_kv && (!diag || key <= pos);
+      z = -INFINITY;
+      dp = 0.f;
+      if (valid) {
+        const float* kr = kb + (int64_t)key * a.ks_t;
+        const float* vr = vb + (int64_t)key * a.vs_t;
+        float acc = 0.f, acd = 0.f;
+        for (int e = 0; e < d; e += 4) {
+          const f32x4 kk = *reinterpret_cast<const f32x4*>(kr + e);
+          const f32x4 vv = *reinterpret_cast<const f32x4*>(vr + e);
+#pragma unroll
+          for (int i = 0; i < 4; i++) {
+            acc = fmaf(qs[wave][e + i], kk[i], acc);
+            acd = fmaf(dos[wave][e + i], vv[i], acd);
+          }
+        }
+        z = fmaf(acc, a.scale, bias);
+        dp = acd;
+      }
+      return valid;
+    };
+    float lse = 0.f, dsum = 0.f, dq0 = 0.f, dq1 = 0.f;
+    for (int pass = 0; pass < 2; pass++) {
+      float m = -INFINITY, l = 0.f, dn = 0.f;
+      int rank = 0;
+      for (int u = 0; u < a.words * 32; u++) {
+        const uint32_t w = mrow[u >> 5];
+        if (w == 0u) { u |= 31; continue; }
+        if (!((w >> (u & 31)) & 1u)) continue;
+        const bool diag = a.causal && u == cw;
+        float bias = 0.f;
+        if (!diag) bias = brow[rank++];
+        float chunk_dz = 0.f;
+        for (int sub = 0; sub < nsub; sub++) {
+          const int kpos0 = u * a.block + sub * 64;
+          float z, dp;
+          const bool valid = key_terms(kpos0, diag, bias, z, dp);
+          if (pass == 0) {
+            const float m_new = fmaxf(m, wave_max(z));
+            if (m_new == -INFINITY) continue;
+            const float p = valid ? expf(z - m_new) : 0.f;
+            const float corr = expf(m - m_new);
+            l = l * corr + wave_sum(p);
+            dn = dn * corr + wave_sum(p * dp);
+            m = m_new;
+            continue;
+          }
+          const float p = valid ? expf(z - lse) : 0.f;
+          const float dz = p * (dp - dsum);
+          chunk_dz += wave_sum(dz);
+          ps[wave][lane] = dz;
+          zs[wave][lane] = p;
+          __builtin_amdgcn_wave_barrier();
+          const int kmax = min(64, a.n_kv - kpos0);
+          for (int kk = 0; kk < kmax; kk++) {
+            const float dzk = ps[wave][kk], pk = zs[wave][kk];
+            if (pk == 0.f && dzk == 0.f) continue;
+            const int64_t key = kpos0 + kk;
+            const float* kr = kb + key * a.ks_t;
+            dq0 = fmaf(dzk, kr[lane], dq0);
+            atomicAdd(dkb + key * a.ks_t + lane, a.scale * dzk * qs[wave][lane]);
+            atomicAdd(dvb + key * a.vs_t + lane, pk * dos[wave][lane]);
+            if (d > 64) {
+              dq1 = fmaf(dzk, kr[lane + 64], dq1);
+              atomicAdd(dkb + key * a.ks_t + lane + 64, a.scale * dzk * qs[wave][lane + 64]);
+              atomicAdd(dvb + key * a.vs_t + lane + 64, pk * dos[wave][lane + 64]);
+            }
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
+        if (pass == 1 && !diag && lane == 0) atomicAdd(a.dbd + base * a.t_all + u, chunk_dz);
+      }
+      if (pass == 0) {
+        lse = m + logf(l);
+        dsum = dn / l;
+      }
+    }
+    const int64_t row = ((int64_t)b * a.h_q + head) * a.n_q + tok;
+    a.dq32[row * d + lane] = a.scale * dq0;
+    if (d > 64) a.dq32[row * d + lane + 64] = a.scale * dq1;
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// dkbar_c = xscale sum over the tokens that route to chunk c and their heads of dx q; folded
+// into the chunk's keys (block mean) or written out.  One workgroup per (chunk, kv-head, batch),
+// thread = head-dimension index.
+__global__ __launch_bounds__(128) void bwd_f32_kbar_kernel(BwdArgs a, int d) {
+  const int c = blockIdx.x, r = blockIdx.y, b = blockIdx.z, t = threadIdx.x;
+  const int i0 = a.causal ? (c + 1 + a.window) * a.block : 0;       // first token with c among its candidates
+  float acc = 0.f;
+  for (int i = i0; i < a.n_q; i++) {
+    const int64_t trow = ((int64_t)b * a.h_kv + r) * a.n_q + i;
+    if (!((a.mask[trow * a.words + (c >> 5)] >> (c & 31)) & 1u)) continue;
+    for (int hl = 0; hl < a.g_q; hl++) {
+      const int head = r * a.g_q + hl;
+      const float dx = a.dxd[(((int64_t)b * a.h_q + head) * a.n_q + i) * a.t_all + c];
+      if (t < d)
+        acc = fmaf(dx, reinterpret_cast<const float*>(a.q)[b * a.qs_b + head * a.qs_h + (int64_t)i * a.qs_t + t], acc);
+    }
+  }
+  if (t >= d) return;
+  const float g = acc * a.xscale;
+  if (a.dkbar_out) {
+    a.dkbar_out[(((int64_t)b * a.h_kv + r) * a.t_c + c) * d + t] = g;
+  } else {
+    float* dk = reinterpret_cast<float*>(a.dk) + b * a.ks_b + r * a.ks_h;
+    for (int j = 0; j < a.block; j++) dk[(int64_t)(c * a.block + j) * a.ks_t + t] += g / (float)a.block;
+  }
+}
+
+template <int D> static hipError_t launch_bwd_f32(const BwdArgs& a, int batch, hipStream_t st) {
+  hipError_t e;
+  hipLaunchKernelGGL(bwd_f32_zero_kernel, dim3(1024), dim3(256), 0, st, a, D, batch);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const size_t nwords = (size_t)batch * a.h_kv * a.n_q * a.t_all;         // the bias gradient, by chunk id
+  hipLaunchKernelGGL(bwd_fill_zero_kernel, dim3(1024), dim3(256), 0, st, reinterpret_cast<uint32_t*>(a.dbd), nwords);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(bwd_f32_row_kernel, dim3(a.n_q, a.h_kv, batch), dim3(256), 0, st, a, D);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if ((e = launch_route_g<D, float>(a, batch, st)) != hipSuccess) return e;
+  if (a.t_c > 0) {
+    hipLaunchKernelGGL(bwd_f32_kbar_kernel, dim3(a.t_c, a.h_kv, batch), dim3(128), 0, st, a, D);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------
 static size_t al256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -922,20 +1098,20 @@ size_t backward_workspace_bytes(const dash_params& p, const Layout& L) {
          al256(rows_q * p.head_dim * 4) + al256((size_t)p.batch * p.h_kv * L.t_all * cwords * 4);
 }
 
-template <int D, int G> static hipError_t launch_route(const BwdArgs& a, int batch, hipStream_t st) {
+template <int D, int G, typename T> static hipError_t launch_route(const BwdArgs& a, int batch, hipStream_t st) {
   const size_t lds = (size_t)G * D * 4 + (size_t)a.t_c * 8 + (size_t)G * 64 * 4 + 64;
-  auto kern = bwd_route_kernel<D, G>;        // at most 29 KB of LDS (t_c <= 2048): no opt-in needed
+  auto kern = bwd_route_kernel<D, G, T>;     // at most 29 KB of LDS (t_c <= 2048): no opt-in needed
   hipLaunchKernelGGL(kern, dim3((unsigned)((size_t)batch * a.h_kv * a.n_q)), dim3(64), lds, st, a);
   return hipGetLastError();
 }
 
-template <int D> static hipError_t launch_route_g(const BwdArgs& a, int batch, hipStream_t st) {
+template <int D, typename T> static hipError_t launch_route_g(const BwdArgs& a, int batch, hipStream_t st) {
   switch (a.g_q) {
-    case 1: return launch_route<D, 1>(a, batch, st);
-    case 2: return launch_route<D, 2>(a, batch, st);
-    case 4: return launch_route<D, 4>(a, batch, st);
-    case 8: return launch_route<D, 8>(a, batch, st);
-    default: return launch_route<D, 16>(a, batch, st);
+    case 1: return launch_route<D, 1, T>(a, batch, st);
+    case 2: return launch_route<D, 2, T>(a, batch, st);
+    case 4: return launch_route<D, 4, T>(a, batch, st);
+    case 8: return launch_route<D, 8, T>(a, batch, st);
+    default: return launch_route<D, 16, T>(a, batch, st);
   }
 }
 
@@ -972,7 +1148,7 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
     hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if ((e = launch_route_g<D>(a, batch, st)) != hipSuccess) return e;
+  if ((e = launch_route_g<D, uint16_t>(a, batch, st)) != hipSuccess) return e;
   {
     const size_t xch = (size_t)2 * 2 * C::NDT * 16 * 64 * 4;
     const size_t tiles = 4 * C::TILE_BYTES;
@@ -1017,6 +1193,8 @@ hipError_t launch_backward(const dash_params& p, const Layout& L, const void* q,
   a.dxd = (float*)(ws + off);    off += al256(rows_q * L.t_all * 4);
   a.dq32 = (float*)(ws + off);   off += al256(rows_q * p.head_dim * 4);
   a.colmask = (uint32_t*)(ws + off);
+  if (p.dtype == DASH_F32)
+    return p.head_dim == 128 ? launch_bwd_f32<128>(a, p.batch, st) : launch_bwd_f32<64>(a, p.batch, st);
   return p.head_dim == 128 ? launch_bwd_t<128>(a, p.batch, st) : launch_bwd_t<64>(a, p.batch, st);
 }
 

@@ -68,7 +68,23 @@ CASES = [
     ("one_token", 2, 4, 2, 1, 128, 64, {}),
     ("exactly_one_chunk", 1, 4, 2, 64, 128, 64, {}),
     ("one_chunk_plus_one", 1, 4, 2, 65, 128, 64, {}),
+    # fp32 tensors (the plain VALU kernels; the routing kernel is the one the bf16 path uses):
+    # the same chain at a tolerance 200 times tighter, every group size of the routing kernel
+    ("f32_gqa2", 1, 4, 2, 512, 128, 64, {"dtype": "fp32"}),
+    ("f32_mha_needles", 2, 2, 2, 448, 128, 64, {"dtype": "fp32", "needles": 2, "offset_sigma": 0.0}),
+    ("f32_gqa4_ragged", 1, 4, 1, 600, 128, 64, {"dtype": "fp32", "offset_sigma": 0.8}),
+    ("f32_gqa8_b128_d64", 1, 8, 1, 768, 64, 128, {"dtype": "fp32", "offset_sigma": 0.8}),
+    ("f32_gqa16", 1, 16, 1, 384, 128, 64, {"dtype": "fp32", "offset_sigma": 0.8}),
+    ("f32_alpha2_window1", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "alpha": 2.0, "gamma": 1.5, "window": 1}),
+    ("f32_alpha125_sigma", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "alpha": 1.25, "sigma": 2.0, "offset_sigma": 1.0}),
+    ("f32_noncausal", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "causal": False, "offset_sigma": 0.8}),
+    ("f32_mha_d64_b64", 1, 2, 2, 320, 64, 64, {"dtype": "fp32", "offset_sigma": 0.8}),
+    ("f32_one_token", 2, 4, 2, 1, 128, 64, {"dtype": "fp32"}),
+    ("f32_one_chunk_plus_one", 1, 4, 2, 65, 128, 64, {"dtype": "fp32"}),
 ]
+# row-wise tolerance by tensor dtype: bf16 rounds P, dz and the outputs to 8 bits of mantissa;
+# the fp32 path keeps everything in fp32 (logits of magnitude ~10 carry ~1e-6 of absolute error)
+TOL = {"bf16": 2e-2, "fp32": 1e-4}
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
@@ -77,11 +93,12 @@ def test_backward_matches_the_oracle(case):
     w = Workload(name, batch, h_q, h_kv, n, n, d, block, seed=17, **extra)
     q, k, v = gen(w)
     gen_do = torch.Generator().manual_seed(99)
-    d_o = torch.randn(q.shape, generator=gen_do).to(torch.bfloat16).to(DEV)
+    d_o = torch.randn(q.shape, generator=gen_do).to(w.torch_dtype).to(DEV)
     run = U.run_prefill(w, q, k, v)
     dq, dk, dv = run_backward(w, q, k, v, run, d_o)
     for t in (dq, dk, dv):
         assert torch.isfinite(t.float()).all(), "an output element was not written or is not finite"
+    tol = TOL[w.dtype]
 
     prm = U.oracle_params(w)
     g = w.g_q
@@ -109,10 +126,14 @@ def test_backward_matches_the_oracle(case):
             ref = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm)
             hi = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, margin_shift=eps)
             lo = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, margin_shift=-eps)
+            # at the fp32 tolerance the rounding of the sums of dz shows too: the mean subtracted
+            # from dd cancels and 1/w amplifies the rest (invisible next to the bf16 tolerance)
+            nz = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, dd_noise=1e-6) \
+                if w.dtype == "fp32" else ref
             for nm, got, j in (("dq", U.to_np(dq[b, sl]), 0), ("dk", U.to_np(dk[b, r]), 1),
                                ("dv", U.to_np(dv[b, r]), 2)):
-                allow = 3.0 * (np.abs(hi[j] - ref[j]) + np.abs(lo[j] - ref[j]))
-                e = rowwise_check(f"{name} {nm}[{b},{r}]", got.astype(np.float64), ref[j], allow)
+                allow = 3.0 * (np.abs(hi[j] - ref[j]) + np.abs(lo[j] - ref[j]) + np.abs(nz[j] - ref[j]))
+                e = rowwise_check(f"{name} {nm}[{b},{r}]", got.astype(np.float64), ref[j], allow, tol)
                 worst[nm] = max(worst.get(nm, 0.0), e)
             if n >= 2 * block:
                 # the path through the routing scores into the block means must be a visible part
@@ -217,17 +238,19 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
     print(f"benchmark shape: {checked} rows checked, {skipped} skipped (support at the band), worst {worst:.2e}")
 
 
-@pytest.mark.parametrize("per_chunk", [False, True], ids=["query_per_head", "query_per_chunk"])
-def test_backward_through_learned_summaries(per_chunk):
+@pytest.mark.parametrize("per_chunk,dtype", [(False, "bf16"), (True, "bf16"), (False, "fp32"), (True, "fp32")],
+                         ids=["query_per_head", "query_per_chunk", "f32_query_per_head", "f32_query_per_chunk"])
+def test_backward_through_learned_summaries(per_chunk, dtype):
     """The trainable Stage 0: forward with dash_kbar_summarize, backward with the
     summaries as an input of their own (dkbar output), then
     dash_kbar_summarize_backward down to the keys and the summary query."""
-    w = Workload("bwd_learned", 1, 4, 2, 512, 512, 128, 64, seed=29, offset_sigma=0.8)
+    w = Workload("bwd_learned", 1, 4, 2, 512, 512, 128, 64, seed=29, offset_sigma=0.8, dtype=dtype)
+    tol = TOL[dtype]
     q, k, v = gen(w)
     t_c = w.n_kv // w.block
     gq = torch.Generator().manual_seed(3)
     qbar = (torch.randn((w.h_kv, t_c, w.head_dim) if per_chunk else (w.h_kv, w.head_dim), generator=gq) * 0.7).to(DEV)
-    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(7)).to(torch.bfloat16).to(DEV)
+    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(7)).to(w.torch_dtype).to(DEV)
     run = U.run_prefill_learned(w, q, k, v, qbar)
     dq, dk, dv = (torch.full_like(t, float("nan")) for t in (q, k, v))
     dkbar = torch.full_like(run.kbar, float("nan"))
@@ -262,11 +285,11 @@ def test_backward_through_learned_summaries(per_chunk):
         got = (U.to_np(dq[0, sl]), U.to_np(dk[0, r]), U.to_np(dv[0, r]), U.to_np(dkbar[0, r]), U.to_np(dqbar[0, r]))
         worst = {}
         for j, nm in enumerate(("dq", "dk", "dv", "dkbar", "dqbar")):
-            worst[nm] = rowwise_check(f"learned {nm}[{r}]", got[j].astype(np.float64), ref[j], allow[j])
+            worst[nm] = rowwise_check(f"learned {nm}[{r}]", got[j].astype(np.float64), ref[j], allow[j], tol)
         if not per_chunk:
             # one query per kv-head: its gradient is the sum over the chunks
             tot_ref, tot_got = ref[4].sum(axis=0), got[4].astype(np.float64).sum(axis=0)
-            assert np.abs(tot_got - tot_ref).max() <= 2e-2 * np.abs(tot_ref).max() + allow[4].sum(axis=0).max()
+            assert np.abs(tot_got - tot_ref).max() <= tol * np.abs(tot_ref).max() + allow[4].sum(axis=0).max()
         # the summary path must be a visible part of dk
         share = np.abs(outs[0][1] - bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm,
                                                             kbar=kbar_ref)[1]).max() / np.abs(ref[1]).max()

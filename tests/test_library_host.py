@@ -137,10 +137,11 @@ def test_backward_argument_errors():
     assert lib.dash_attn_backward(ctypes.byref(p), *ptrs, 256, need - 1, None) == -3
     assert lib.dash_attn_backward(ctypes.byref(p), *ptrs, 257, need, None) == -3
     n = ctypes.c_size_t(0)
-    for kw in (dict(dtype=0), dict(n_q=512, n_kv=1024)):            # fp32 tensors; a chunked prefill
-        pu = params(**kw)
-        assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(pu), ctypes.byref(n)) == -2
-        assert lib.dash_attn_backward(ctypes.byref(pu), *ptrs, 256, 1 << 40, None) == -2
+    pu = params(n_q=512, n_kv=1024)                                 # a chunked prefill
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(pu), ctypes.byref(n)) == -2
+    assert lib.dash_attn_backward(ctypes.byref(pu), *ptrs, 256, 1 << 40, None) == -2
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(params(dtype=0)), ctypes.byref(n)) == 0   # fp32 tensors
+    assert n.value == need
     assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(p), None) == -1
     big = params(h_q=16, h_kv=1, n_q=131072, n_kv=131072)          # a 16-head slice of q spans 512 MiB: fine
     assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(big), ctypes.byref(n)) == 0
