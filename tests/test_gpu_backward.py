@@ -79,6 +79,8 @@ CASES = [
     ("f32_alpha125_sigma", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "alpha": 1.25, "sigma": 2.0, "offset_sigma": 1.0}),
     ("f32_noncausal", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "causal": False, "offset_sigma": 0.8}),
     ("f32_mha_d64_b64", 1, 2, 2, 320, 64, 64, {"dtype": "fp32", "offset_sigma": 0.8}),
+    # the shape of the fp32 single-head non-causal configuration
+    ("f32_single_head_1024", 1, 1, 1, 1024, 64, 64, {"dtype": "fp32", "causal": False, "offset_sigma": 0.5}),
     ("f32_one_token", 2, 4, 2, 1, 128, 64, {"dtype": "fp32"}),
     ("f32_one_chunk_plus_one", 1, 4, 2, 65, 128, 64, {"dtype": "fp32"}),
 ]
