@@ -83,6 +83,8 @@ CASES = [
     ("f32_single_head_1024", 1, 1, 1, 1024, 64, 64, {"dtype": "fp32", "causal": False, "offset_sigma": 0.5}),
     ("f32_window2_b128", 1, 4, 2, 768, 128, 128, {"dtype": "fp32", "window": 2, "offset_sigma": 0.8}),
     ("f32_sparse_gamma3_sigma03", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "gamma": 3.0, "sigma": 0.3, "offset_sigma": 1.0}),
+    ("f32_alpha3", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "alpha": 3.0, "offset_sigma": 0.8}),
+    ("f32_alpha105", 1, 4, 2, 512, 128, 64, {"dtype": "fp32", "alpha": 1.05, "offset_sigma": 0.8}),
     ("f32_one_token", 2, 4, 2, 1, 128, 64, {"dtype": "fp32"}),
     ("f32_one_chunk_plus_one", 1, 4, 2, 65, 128, 64, {"dtype": "fp32"}),
 ]
