@@ -311,13 +311,15 @@ def test_backward_through_learned_summaries(per_chunk, dtype):
         print(f"learned summaries, kv-head {r}: " + " ".join(f"{a} {b:.2e}" for a, b in worst.items()))
 
 
-def test_forward_and_backward_replay_from_a_captured_graph():
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_forward_and_backward_replay_from_a_captured_graph(dtype):
     """Neither call allocates, synchronises or clears memory with a memset node, so a
     training step can be captured once and replayed: three replays with new inputs in
-    the same buffers, eager work in between, each equal to the eager results."""
-    w = Workload("train_graph", 2, 8, 2, 700, 700, 128, 64, seed=19, offset_sigma=0.8)
+    the same buffers, eager work in between, each equal to the eager results (fp32
+    tensors: the forward bit for bit, the gradients up to the order of their atomic sums)."""
+    w = Workload("train_graph", 2, 8, 2, 700, 700, 128, 64, seed=19, offset_sigma=0.8, dtype=dtype)
     q, k, v = gen(w)
-    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(2)).to(torch.bfloat16).to(DEV)
+    d_o = torch.randn(q.shape, generator=torch.Generator().manual_seed(2)).to(w.torch_dtype).to(DEV)
     o = torch.empty_like(q)
     p = B.make_params(q, k, v, o, w.block, w.alpha, w.gamma, w.sigma, w.causal)
     kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=DEV)
@@ -328,6 +330,11 @@ def test_forward_and_backward_replay_from_a_captured_graph():
     def step():
         B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws)
         B.dash_attn_backward(p, q, k, v, d_o, kbar, lists, dq, dk, dv, wsb)
+
+    def same(got, want, exact):
+        if exact:
+            return torch.equal(got, want)
+        return bool(((got - want).abs() <= 1e-3 * want.abs().amax(dim=-1, keepdim=True) + 1e-6).all())
 
     step()                                                     # warm-up outside the capture
     torch.cuda.synchronize()
@@ -351,6 +358,6 @@ def test_forward_and_backward_replay_from_a_captured_graph():
             t.zero_()
         step()                                                 # eager, same inputs
         torch.cuda.synchronize()
-        for a_, b_ in zip(got, (o, dq, dk, dv)):
-            assert torch.equal(a_, b_), rep
+        for j, (a_, b_) in enumerate(zip(got, (o, dq, dk, dv))):
+            assert same(a_, b_, dtype == "bf16" or j == 0), (rep, j)
         assert dq.float().abs().max() > 0 and torch.isfinite(dk.float()).all()
