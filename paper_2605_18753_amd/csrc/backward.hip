@@ -1,4 +1,5 @@
-// Backward pass of the prefill path (bf16): gradients of the block-sparse
+// Backward pass of the prefill path (bf16 on the matrix cores; fp32 tensors on
+// plain kernels at the end of the file): gradients of the block-sparse
 // attention with the routing prior with respect to q, k and v, including the
 // path through the bias into the Stage-1 entmax weights and from there into the
 // block-mean summaries (end of Sec. 3.3: the output is differentiable in q, k, v
@@ -27,6 +28,8 @@
 //                  dx per head and chunk, the routing part of dq, final dq.
 //   bwd_kv_kernel  owns a 64-key tile, walks the row tiles that attend its chunk and
 //                  accumulates dK, dV and the chunk's dkbar without atomics.
+//   bwd_f32_*      the same chain for fp32 tensors on the VALU (row kernel with atomics,
+//                  the routing kernel above, a per-chunk dkbar kernel).
 // MFMA operand layouts are those of the forward kernel: every product is
 // arranged so that the accumulator of the first product is directly the
 // B operand of the second; the transposed operand comes from LDS through the
