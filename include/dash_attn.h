@@ -14,13 +14,19 @@
  *
  * Conventions shared by every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
- *     allocates no device memory, keeps no state between calls, never
- *     synchronises, and enqueues all work on `stream` (a hipStream_t passed as
- *     void*; NULL = the default stream).
+ *     allocates no device memory, never synchronises, reads no environment
+ *     variable, and enqueues all work on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).  Nothing a call computes depends on an earlier
+ *     call: the only thing the library remembers is, per device, that a kernel's
+ *     one-time opt-in to more than 64 KB of LDS has been made (thread-safe).
+ *     Entry points may be called from several threads.
  *   - Tensors are [batch, head, token, head_dim] with head_dim contiguous; the
  *     other three strides are given in ELEMENTS in dash_params.  Rows must be
  *     16-byte aligned (base pointers 16-byte aligned, strides multiples of 8
- *     elements for bf16 / 4 for fp32).
+ *     elements for bf16 / 4 for fp32).  bf16 tensors: one (batch, kv-head) slice
+ *     of q, k, v, o (for q and o: the g_q heads of a kv-head) must span less than
+ *     2 GiB, as the kernels address it with 32-bit byte offsets
+ *     (DASH_EUNSUPPORTED otherwise).
  *   - Return value: DASH_OK (0) or a negative dash_status.  On a non-zero return
  *     nothing was enqueued (validation errors) or the outputs are undefined
  *     (DASH_ELAUNCH).  No exceptions or aborts cross this boundary.
@@ -225,9 +231,8 @@ int dense_attn(const dash_params* p, const void* q, const void* k, const void* v
  *                  calls in flight must not share it)
  * For alpha > 2 the entmax slope is unbounded at the edge of the support, so rows
  * with a chunk close to its threshold have gradients only as accurate as the fp32
- * scores allow (checked against the oracle up to alpha = 3).
- * n_q == n_kv only (DASH_EUNSUPPORTED otherwise, also when a (batch, kv-head)
- * slice of a bf16 tensor spans 2 GiB or more).  bf16 tensors take the matrix-core
+ * scores allow; alpha <= 3 only (checked against the oracle up to there;
+ * DASH_EUNSUPPORTED above).  n_q == n_kv only (DASH_EUNSUPPORTED otherwise).  bf16 tensors take the matrix-core
  * kernels; fp32 tensors take plain fp32 kernels that accumulate dk and dv with
  * atomics (a correctness vehicle like the fp32 forward, sums in no fixed order);
  * DASH_EINVAL for a NULL pointer. */

@@ -4,7 +4,7 @@ Plain numpy, fp64, one query row at a time, the chain rule applied step by
 step to the forward path of dash_oracle.dash_row_at; nothing in the product
 path may import it.  It shares no code with the HIP path.
 
-The paper states that Eq. 6 is differentiable with respect to q, k, v and the
+The paper states that the Stage-2 output (Sec. 3.3) is differentiable with respect to q, k, v and the
 prior, that the gradient reaches the Stage-1 entmax weights and, through them,
 the Stage-0 summaries (end of Sec. 3.3), and that the backward pass reuses the
 forward's chunk mask because the entmax Jacobian is sparse (Sec. 3.5 / App. on
@@ -73,42 +73,20 @@ def entmax_jacobian_vjp(x: np.ndarray, tau: float, alpha: float, dw: np.ndarray)
 
 
 def backward_row(qh: np.ndarray, k: np.ndarray, v: np.ndarray, kbar: np.ndarray, d_o: np.ndarray,
-                 prm: orc.DashParams, pos: int, dk: np.ndarray, dv: np.ndarray, dkbar: np.ndarray,
-                 margin_shift: float = 0.0, dd_noise: float = 0.0):
+                 prm: orc.DashParams, pos: int, dk: np.ndarray, dv: np.ndarray, dkbar: np.ndarray):
     """Backward of dash_oracle.dash_row_at for the g_q heads qh [g_q, d] at
     position pos with upstream gradient d_o [g_q, d].  Adds this row's
     contributions into dk, dv [n_kv, d] and dkbar [T_c, d]; returns
-    (dq [g_q, d], dx [g_q, n_cand], dd [len(routed)]).
-
-    margin_shift (a test aid, 0 for the gradient itself) evaluates the prior (the
-    bias inside the attention as well as its derivative) and the entmax Jacobian
-    with every margin x - tau moved by that amount, the support kept: the change of the result measures how an error of that size in
-    a lower-precision evaluation of the scores propagates (ln w and 1/w are
-    singular at the edge of the support).
-
-    dd_noise (a test aid too, 0 for the gradient itself) adds dd_noise * sum |dz|
-    to the bias gradient of the routed chunk with the smallest weight w before the
-    prior step: dlnw subtracts the mean of dd, which cancels (exactly, when every
-    attended token lies in a routed chunk), and dw = dlnw / w amplifies what is
-    left the most where w is smallest, so the change of the result measures how a
-    rounding error of that relative size in the sums of dz propagates."""
+    (dq [g_q, d], dx [g_q, n_cand], dd [len(routed)])."""
     qh = np.asarray(qh, dtype=np.float64)
     d_o = np.asarray(d_o, dtype=np.float64)
     g_q, d = qh.shape
     rr = orc.dash_row_at(qh, k, v, kbar, prm, pos)
     scale = prm.scale if prm.scale is not None else 1.0 / math.sqrt(d)
     blk = prm.block
-    # test aid only: scores and prior with every margin of the support moved by margin_shift
-    w_used, x_used, bias_used = rr.w, rr.x, rr.bias
-    if margin_shift != 0.0 and len(rr.routed):
-        p = 1.0 / (prm.alpha - 1.0)
-        sup = rr.x > rr.tau[:, None]
-        x_used = np.where(sup, np.maximum(rr.x + margin_shift, rr.tau[:, None] + 1e-12), rr.x)
-        w_used = (np.where(sup, x_used - rr.tau[:, None], 0.0) ** p).sum(axis=0) / float(g_q)
-        bias_used = orc.prior_bias(w_used, prm.sigma)[1]
     # the attended tokens and their bias, in the forward's order
     tok = [np.arange(c * blk, (c + 1) * blk) for c in rr.routed]
-    dtok = [np.full(blk, b) for b in bias_used]
+    dtok = [np.full(blk, b) for b in rr.bias]
     chunk_of = [np.full(blk, j) for j in range(len(rr.routed))]
     if rr.diag[1] > rr.diag[0]:
         tok.append(np.arange(rr.diag[0], rr.diag[1]))
@@ -122,14 +100,12 @@ def backward_row(qh: np.ndarray, k: np.ndarray, v: np.ndarray, kbar: np.ndarray,
 
     dq = np.zeros((g_q, d))
     dd = np.zeros(len(rr.routed))
-    abs_dz = 0.0
     for h in range(g_q):
         z = kk @ qh[h] * scale + dtok
         e = np.exp(z - z.max())
         P = e / e.sum()
         dP = vv @ d_o[h]
         dz = P * (dP - P @ dP)
-        abs_dz += np.abs(dz).sum()
         dq[h] += scale * (kk.T @ dz)
         np.add.at(dk, tok, scale * np.outer(dz, qh[h]))
         np.add.at(dv, tok, np.outer(P, d_o[h]))
@@ -138,22 +114,19 @@ def backward_row(qh: np.ndarray, k: np.ndarray, v: np.ndarray, kbar: np.ndarray,
 
     dx = np.zeros((g_q, rr.n_cand))
     if len(rr.routed):
-        if dd_noise != 0.0:
-            dd[np.argmin(rr.w[rr.routed])] += dd_noise * abs_dz
         dlnw = (dd - dd.mean()) / prm.sigma
         dw = np.zeros(rr.n_cand)
-        dw[rr.routed] = dlnw / w_used[rr.routed]
+        dw[rr.routed] = dlnw / rr.w[rr.routed]
         c_x = prm.gamma * (prm.alpha - 1.0) * scale
         for h in range(g_q):
-            dx[h] = entmax_jacobian_vjp(x_used[h], rr.tau[h], prm.alpha, dw / float(g_q))
+            dx[h] = entmax_jacobian_vjp(rr.x[h], rr.tau[h], prm.alpha, dw / float(g_q))
             dq[h] += c_x * (dx[h] @ np.asarray(kbar[:rr.n_cand], dtype=np.float64))
             dkbar[:rr.n_cand] += c_x * np.outer(dx[h], qh[h])
     return dq, dx, dd
 
 
 def dash_backward_group(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.ndarray,
-                        prm: orc.DashParams, kbar: Optional[np.ndarray] = None, margin_shift: float = 0.0,
-                        dd_noise: float = 0.0) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+                        prm: orc.DashParams, kbar: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
     """Backward for one (batch, kv-head) pair: q, d_o [g_q, n_q, d]; k, v
     [n_kv, d]; query t sits at position n_kv - n_q + t.  kbar None: block-mean
     summaries, whose gradient is folded into dk; otherwise the given summaries
@@ -172,8 +145,7 @@ def dash_backward_group(q: np.ndarray, k: np.ndarray, v: np.ndarray, d_o: np.nda
     dv = np.zeros_like(v)
     dkbar = np.zeros_like(np.asarray(kbar, dtype=np.float64))
     for t in range(n_q):
-        dq[:, t], _, _ = backward_row(q[:, t], k, v, kbar, d_o[:, t], prm, n_kv - n_q + t, dk, dv, dkbar,
-                                      margin_shift, dd_noise)
+        dq[:, t], _, _ = backward_row(q[:, t], k, v, kbar, d_o[:, t], prm, n_kv - n_q + t, dk, dv, dkbar)
     if fold:
         blk = prm.block
         for c in range(dkbar.shape[0]):

@@ -16,14 +16,17 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-w",
 def build(verbose: bool = True, lib: str = LIB, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     extra = list(extra) + os.environ.get("DASH_EXTRA_FLAGS", "").split()
-    objs = []
-    for s in SOURCES:
+    objs, procs = [], []
+    for s in SOURCES:   # one compiler process per source file, all at once
         o = os.path.join(CSRC, s.replace(".hip", ".o"))
         cmd = [hipcc, *[f for f in FLAGS if f != "-shared"], *extra, "-c", os.path.join(CSRC, s), "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
-        subprocess.run(cmd, check=True)
+        procs.append((cmd, subprocess.Popen(cmd)))
         objs.append(o)
+    for cmd, pr in procs:
+        if pr.wait() != 0:
+            raise subprocess.CalledProcessError(pr.returncode, cmd)
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -52,8 +52,7 @@ int make_layout(const dash_params* p, Layout* L, bool routing) {
   int splits = 1;
   if (decode_mfma) {
     const int pairs = p->batch * p->h_kv;
-    const char* env = getenv("DASH_DECODE_WGS");   // tuning aid: target workgroup count
-    const int target = env ? atoi(env) : 512;
+    const int target = 512;   // workgroups per launch: two per CU
     splits = (target + pairs - 1) / pairs;
     if (splits > 64) splits = 64;
     if (splits > L->t_all) splits = L->t_all;
@@ -71,6 +70,16 @@ int make_layout(const dash_params* p, Layout* L, bool routing) {
   L->off_part = off;
   if (decode_mfma) off += align256((size_t)p->batch * p->h_kv * splits * g * (p->head_dim + 2) * 4);
   L->total = off > 0 ? off : 256;
+  if (p->dtype == DASH_BF16) {
+    // the bf16 kernels address one (batch, kv-head) slice of every tensor with 32-bit byte
+    // offsets and a 32-bit buffer size: a slice must span less than 2 GiB
+    const int64_t lim = (int64_t)1 << 31;
+    const int64_t nq = p->n_q, nk = p->n_kv, d = p->head_dim;
+    if (((g - 1) * p->q_stride[1] + (nq - 1) * p->q_stride[2] + d) * 2 >= lim ||
+        ((g - 1) * p->o_stride[1] + (nq - 1) * p->o_stride[2] + d) * 2 >= lim ||
+        ((nk - 1) * p->k_stride[2] + d) * 2 >= lim || ((nk - 1) * p->v_stride[2] + d) * 2 >= lim)
+      return DASH_EUNSUPPORTED;
+  }
   return DASH_OK;
 }
 
@@ -262,14 +271,9 @@ static int backward_layout(const dash_params* p, Layout* L) {
   int rc = make_layout(p, L);
   if (rc != DASH_OK) return rc;
   if (p->n_q != p->n_kv) return DASH_EUNSUPPORTED;
-  if (p->dtype == DASH_F32) return DASH_OK;      // plain pointers with 64-bit offsets
-  // the bf16 kernels address a (batch, kv-head) slice of every tensor with 32-bit byte offsets
-  const int64_t lim = (int64_t)1 << 31;
-  const int64_t g = L->g_q, n = p->n_q, d = p->head_dim;
-  if (((g - 1) * p->q_stride[1] + (n - 1) * p->q_stride[2] + d) * 2 >= lim ||
-      ((g - 1) * p->o_stride[1] + (n - 1) * p->o_stride[2] + d) * 2 >= lim ||
-      ((n - 1) * p->k_stride[2] + d) * 2 >= lim || ((n - 1) * p->v_stride[2] + d) * 2 >= lim)
-    return DASH_EUNSUPPORTED;
+  // p = 1/(alpha-1) < 1/2: the entmax slope is unbounded at the edge of the support and the
+  // fp32 scores no longer carry the gradient of rows with a chunk near its threshold
+  if (p->alpha > 3.f) return DASH_EUNSUPPORTED;
   return DASH_OK;
 }
 

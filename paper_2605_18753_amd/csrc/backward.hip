@@ -1118,18 +1118,9 @@ template <int D, typename T> static hipError_t launch_route_g(const BwdArgs& a, 
   }
 }
 
-// more than 64 KB of dynamic LDS needs an opt-in, once per kernel (not a stream operation, so it
-// is done on the first call only and a later call can be captured into a graph)
-static hipError_t allow_lds(const void* kern, size_t bytes, bool& done) {
-  if (done) return hipSuccess;
-  const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  done = e == hipSuccess;
-  return e;
-}
-
 template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hipStream_t st) {
   using C = BCfg<D>;
-  static bool done_lse = false, done_grad = false, done_kv = false;
+  static LdsOptIn done_lse, done_grad, done_kv;
   hipError_t e;
   {
     const size_t nwords = (size_t)a.hb * a.t_all * a.cwords;
@@ -1140,14 +1131,14 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
   {
     const size_t lds = 2 * C::TILE_BYTES + 5 * 64 * 4;
     auto kern = bwd_q_kernel<D, false>;
-    if ((e = allow_lds((const void*)kern, lds, done_lse)) != hipSuccess) return e;
+    if ((e = allow_dyn_lds((const void*)kern, lds, done_lse)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
     const size_t lds = 4 * C::TILE_BYTES + 5 * 64 * 4;
     auto kern = bwd_q_kernel<D, true>;
-    if ((e = allow_lds((const void*)kern, lds, done_grad)) != hipSuccess) return e;
+    if ((e = allow_dyn_lds((const void*)kern, lds, done_grad)) != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
@@ -1158,7 +1149,7 @@ template <int D> static hipError_t launch_bwd_t(const BwdArgs& a, int batch, hip
     // tiles (reused for the end-of-kernel exchange), 4 per-row scalar arrays, dkbar and its partials
     const size_t lds = (xch > tiles ? xch : tiles) + 4 * 64 * 4 + D * 4 + (size_t)(256 / C::NCH) * D * 4;
     auto kern = bwd_kv_kernel<D>;
-    if ((e = allow_lds((const void*)kern, lds, done_kv)) != hipSuccess) return e;
+    if ((e = allow_dyn_lds((const void*)kern, lds, done_kv)) != hipSuccess) return e;
     const int ktiles = (a.n_kv + 63) / 64;
     hipLaunchKernelGGL(kern, dim3(ktiles * a.hb), dim3(256), lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;

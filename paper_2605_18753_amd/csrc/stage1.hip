@@ -695,12 +695,11 @@ hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const voi
   return hipGetLastError();
 }
 
-template <typename K>
-static hipError_t launch_route_k(K kern, const S1Args& a, dim3 grid, size_t lds, hipStream_t st) {
-  if (lds > 48 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
+template <auto kern>
+static hipError_t launch_route_k(const S1Args& a, dim3 grid, size_t lds, hipStream_t st) {
+  // the row length of the launch sizes the LDS: opt in to the whole compute unit's once
+  static LdsOptIn opt_in;   // one per kernel (kern is a template argument)
+  if (hipError_t e = allow_dyn_lds((const void*)kern, kMaxDynLds, opt_in); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
   return hipGetLastError();
 }
@@ -751,11 +750,7 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
   // row: the early ranges get more rows per workgroup (fewer re-reads of the summaries)
   // and more workgroups per CU.  Measured: 96k tokens, GQA group 16: 25.9 -> 17.9 ms;
   // 128k tokens, chunk 128: 12.5 -> 11.0 ms; no effect at 512 chunks or fewer.
-  int nseg = (p.causal && L.t_c >= 1024 && p.n_q > 1 && !L.seq_lens) ? 4 : 1;
-  if (const char* env = getenv("DASH_S1_SEGS")) {   // tuning aid: number of token ranges
-    const int v = atoi(env);
-    if (v >= 1 && v <= 64 && p.causal && !L.seq_lens) nseg = v;
-  }
+  const int nseg = (p.causal && L.t_c >= 1024 && p.n_q > 1 && !L.seq_lens) ? 4 : 1;
   for (int sg = nseg - 1; sg >= 0; sg--) {
     const int t0 = (int)(((int64_t)p.n_q * sg / nseg + 63) / 64 * 64);
     const int t1 = sg == nseg - 1 ? p.n_q : (int)(((int64_t)p.n_q * (sg + 1) / nseg + 63) / 64 * 64);
@@ -779,12 +774,12 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
     const size_t lds = (size_t)16 * mt * a.ld * 4;
     hipError_t e;
     if (!mfma) {
-      e = p.head_dim == 128 ? launch_route_k(s1_route_kernel<1, 128, false>, a, grid, lds, st)
-                            : launch_route_k(s1_route_kernel<1, 64, false>, a, grid, lds, st);
+      e = p.head_dim == 128 ? launch_route_k<s1_route_kernel<1, 128, false>>(a, grid, lds, st)
+                            : launch_route_k<s1_route_kernel<1, 64, false>>(a, grid, lds, st);
     } else {
 #define DASH_RT(MT_)                                                                     \
-  (p.head_dim == 128 ? launch_route_k(s1_route_kernel<MT_, 128, true>, a, grid, lds, st) \
-                     : launch_route_k(s1_route_kernel<MT_, 64, true>, a, grid, lds, st))
+  (p.head_dim == 128 ? launch_route_k<s1_route_kernel<MT_, 128, true>>(a, grid, lds, st) \
+                     : launch_route_k<s1_route_kernel<MT_, 64, true>>(a, grid, lds, st))
       e = mt == 4 ? DASH_RT(4) : (mt == 2 ? DASH_RT(2) : DASH_RT(1));
 #undef DASH_RT
     }

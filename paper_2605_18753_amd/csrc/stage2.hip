@@ -7,7 +7,7 @@
 // wave w owns 32 rows = all g_q heads of 32/g_q consecutive tokens.  The
 // workgroup walks the union of its tokens' chunk masks in ascending order.
 // Every 64-key tile of K and V is copied once from global memory straight into
-// LDS (global_load_lds_dwordx4, no staging registers), two stages deep: the copy
+// LDS (buffer_load_dwordx4 ... lds, no staging registers), two stages deep: the copy
 // of tile j+1 is in flight while tile j is computed.  A wave skips the MFMA work
 // of a chunk none of its tokens kept; rows of a wave that did not keep a chunk
 // get bias -inf for it, which keeps the per-token result exact.
@@ -434,13 +434,8 @@ template <int D, bool DENSE>
 static hipError_t launch_s2_t(const S2Args& a, hipStream_t st) {
   using C = S2Cfg<D>;
   auto kern = s2_attend_kernel<D, DENSE>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOptIn opt_in;
+  if (hipError_t e = allow_dyn_lds((const void*)kern, C::LDS_BYTES, opt_in); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), C::LDS_BYTES, st, a);
   return hipGetLastError();
 }

@@ -299,13 +299,8 @@ template <int D, bool DENSE>
 static hipError_t launch_decode_t(const S2Args& a, hipStream_t st) {
   using C = DecCfg<D>;
   auto kern = s2_decode_kernel<D, DENSE>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)C::LDS_BYTES);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOptIn opt_in;
+  if (hipError_t e = allow_dyn_lds((const void*)kern, C::LDS_BYTES, opt_in); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.hb), dim3(256), C::LDS_BYTES, st, a);
   return hipGetLastError();
 }

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import bwd_sensitivity as S
 import parity_util as U
 from oracle import dash_oracle as orc
 from oracle import dash_oracle_bwd as bwd
@@ -30,19 +31,32 @@ def run_backward(w, q, k, v, run, d_o):
     return dq, dk, dv
 
 
+# Limits of the comparison, in units the report of bwd_sensitivity.rowwise_report prints:
+#   every element is held to tol * scale_row + allowance (allowance = the change of the exact
+#   gradient under an fp32-sized perturbation of the summaries and of dO, times 3);
+#   an element whose allowance is below CAP * tol * scale_row must pass with it; the others (the exact
+#   gradient itself is that ill-conditioned there) are counted and may be at most ILL_MAX of all;
+#   at most NEED_MAX of the elements may need any allowance at all.
+CAP, NEED_MAX, ILL_MAX = 10.0, 0.01, 0.002
+
+
 def rowwise_check(name, got, ref, allow, tol=2e-2):
-    """Row by row (last axis = head_dim): |got - ref| <= tol * scale_row + allow,
-    scale_row = the row's largest reference magnitude, floored at a tenth of
-    the median over rows so that near-zero rows are not held to a relative bar."""
-    rowmax = np.abs(ref).max(axis=-1, keepdims=True)
-    floor = 0.1 * np.median(rowmax)
-    bound = tol * np.maximum(rowmax, floor) + allow
-    err = np.abs(got - ref)
-    bad = err > bound
-    assert not bad.any(), (f"{name}: {int(bad.sum())} elements off, worst excess "
-                           f"{(err - bound).max():.3e} at {np.unravel_index(np.argmax(err - bound), err.shape)}, "
-                           f"ref there {ref[np.unravel_index(np.argmax(err - bound), err.shape)]:.3e}")
-    return float((err / np.maximum(np.maximum(rowmax, floor), 1e-300)).max())
+    rep = S.rowwise_report(got, ref, allow, tol, CAP)
+    msg = f"{name}: " + " ".join(f"{a} {b:.2e}" for a, b in rep.items())
+    assert rep["excess"] <= 0.0 and rep["capped_excess"] <= 0.0, msg
+    assert rep["need_allow"] <= NEED_MAX and rep["ill"] <= ILL_MAX, msg
+    return rep
+
+
+def merge(worst, nm, rep):
+    w = worst.setdefault(nm, dict(rep))
+    for a, b in rep.items():
+        w[a] = max(w[a], b)
+
+
+def fmt(worst):
+    return "; ".join(f"{nm}: plain {r['plain_worst']:.2e} median {r['median']:.2e} p99 {r['p99']:.2e} "
+                     f"need_allow {r['need_allow']:.1e} ill {r['ill']:.1e}" for nm, r in worst.items())
 
 
 CASES = [
@@ -125,22 +139,18 @@ def test_backward_matches_the_oracle(case):
                 mism += got != set(rr.routed.tolist())
                 if rr.n_cand:
                     xmax = max(xmax, float(np.abs(rr.x).max()))
-            assert mism == 0, f"{mism} rows route differently on the two sides: choose another seed"
+            # gradients are compared inside one support (a precondition of the comparison, not of the
+            # kernel: the forward tests cover the band around the threshold)
+            assert mism == 0, f"{mism} rows route differently on the two sides"
             sl = slice(r * g, (r + 1) * g)
-            # fp32 scores carry an error of a few units in the last place of the largest score
-            eps = 1e-6 * xmax
+            # fp32 scores and sums of dz carry an error of about 1e-6 of their magnitude
             ref = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm)
-            hi = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, margin_shift=eps)
-            lo = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, margin_shift=-eps)
-            # at the fp32 tolerance the rounding of the sums of dz shows too: the mean subtracted
-            # from dd cancels and 1/w amplifies the rest (invisible next to the bf16 tolerance)
-            nz = bwd.dash_backward_group(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, dd_noise=1e-6) \
-                if w.dtype == "fp32" else ref
+            pair = S.perturbed_pair(qn[b, sl], kn[b, r], vn[b, r], don[b, sl], prm, eps=1e-6,
+                                    seed=b * 16 + r)
+            allow = S.allowance(ref, pair)
             for nm, got, j in (("dq", U.to_np(dq[b, sl]), 0), ("dk", U.to_np(dk[b, r]), 1),
                                ("dv", U.to_np(dv[b, r]), 2)):
-                allow = 3.0 * (np.abs(hi[j] - ref[j]) + np.abs(lo[j] - ref[j]) + np.abs(nz[j] - ref[j]))
-                e = rowwise_check(f"{name} {nm}[{b},{r}]", got.astype(np.float64), ref[j], allow, tol)
-                worst[nm] = max(worst.get(nm, 0.0), e)
+                merge(worst, nm, rowwise_check(f"{name} {nm}[{b},{r}]", got.astype(np.float64), ref[j], allow[j], tol))
             if n >= 2 * block:
                 # the path through the routing scores into the block means must be a visible part
                 # of dk, or the comparison above would not notice its absence
@@ -148,7 +158,7 @@ def test_backward_matches_the_oracle(case):
                 rowmax = np.abs(ref[1]).max(axis=-1)
                 share = np.abs(ref[1] - direct).max(axis=-1) / np.maximum(rowmax, 0.1 * np.median(rowmax))
                 assert share.max() > 0.05, share.max()
-    print(f"{name}: worst row-relative error dq {worst['dq']:.2e} dk {worst['dk']:.2e} dv {worst['dv']:.2e}")
+    print(f"{name}: {fmt(worst)}")
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
@@ -211,7 +221,7 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
     t_all = B.list_stride(run.params)
     rng = np.random.default_rng(1)
     checked = skipped = 0
-    worst = 0.0
+    worst = {}
     # the 128k shape costs the oracle about 0.1 s per row: one kv-head and sampled rows only there
     light = w.n_q > 65536
     groups = ((0, 3),) if light else ((0, 0), (w.batch - 1, w.h_kv - 1), (w.batch // 2, w.h_kv // 2))
@@ -224,6 +234,7 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
         tail_ok = not light
         dk_ref, dv_ref, dkb = np.zeros_like(kn), np.zeros_like(vn), np.zeros_like(kbar)
         scratch = (np.zeros_like(kn), np.zeros_like(vn), np.zeros_like(kbar))    # sums nobody reads
+        gots, refs, allows = [], [], []
         for i in rows:
             qh = U.to_np(q[b, sl, i]).astype(np.float64)
             doh = U.to_np(d_o[b, sl, i]).astype(np.float64)
@@ -232,24 +243,24 @@ def test_backward_at_the_benchmark_shape_on_sampled_rows(which):
             same = set(np.nonzero(bits[:rr.n_cand])[0].tolist()) == set(rr.routed.tolist())
             scr_k, scr_v, scr_b = (dk_ref, dv_ref, dkb) if i >= n - blk else scratch
             ref_dq, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, scr_k, scr_v, scr_b)
-            hi, _, _ = bwd.backward_row(qh, kn, vn, kbar, doh, prm, i, *scratch, margin_shift=1e-6)
             if not same:
                 skipped += 1
                 tail_ok = tail_ok and i < n - blk
                 continue
-            got = U.to_np(dq[b, sl, i]).astype(np.float64)
-            allow = 6.0 * np.abs(hi - ref_dq)
-            worst = max(worst, rowwise_check(f"dq[{b},{r},{i}]", got, ref_dq, allow))
+            pair = S.perturbed_row_pair(qh, kn, vn, kbar, doh, prm, i, eps=1e-6, seed=i)
+            gots.append(U.to_np(dq[b, sl, i]).astype(np.float64))
+            refs.append(ref_dq)
+            allows.append(S.allowance([ref_dq], [[pair[0]], [pair[1]]])[0])
             checked += 1
+        merge(worst, "dq", rowwise_check(f"dq[{b},{r}]", np.stack(gots), np.stack(refs), np.stack(allows)))
         if tail_ok:
             # keys of the last (complete) chunk: no later row routes to it, so these sums are complete
             last = slice(n - blk, n)
             for nm, got, ref in (("dk", dk, dk_ref), ("dv", dv, dv_ref)):
-                e = rowwise_check(f"{nm}[{b},{r},last chunk]", U.to_np(got[b, r, last]).astype(np.float64), ref[last],
-                                  np.zeros_like(ref[last]))
-                worst = max(worst, e)
+                merge(worst, nm, rowwise_check(f"{nm}[{b},{r},last chunk]", U.to_np(got[b, r, last]).astype(np.float64),
+                                               ref[last], np.zeros_like(ref[last])))
     assert checked >= (20 if light else 150) and skipped <= 6, (checked, skipped)
-    print(f"benchmark shape: {checked} rows checked, {skipped} skipped (support at the band), worst {worst:.2e}")
+    print(f"benchmark shape: {checked} rows checked, {skipped} skipped (support at the band); {fmt(worst)}")
 
 
 @pytest.mark.parametrize("per_chunk,dtype", [(False, "bf16"), (True, "bf16"), (False, "fp32"), (True, "fp32")],
@@ -288,27 +299,28 @@ def test_backward_through_learned_summaries(per_chunk, dtype):
             bits = U.mask_bits(run.lists.mask[0, r, i].cpu().numpy(), t_all)
             assert set(np.nonzero(bits[:rr.n_cand])[0].tolist()) == set(rr.routed.tolist()), "choose another seed"
         sl = slice(r * g, (r + 1) * g)
-        outs = []
-        for shift in (0.0, 1e-6, -1e-6):
-            rq, rk, rv, rkb = bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm, kbar=kbar_ref,
-                                                      margin_shift=shift)
+        def through_stage0(grads):
+            rq, rk, rv, rkb = grads
             sk, sq = bwd.local_attention_summaries_backward(kn[0, r], qbn[r], blk, rkb)
-            outs.append((rq, rk + sk, rv, rkb, sq))
-        ref = outs[0]
-        allow = [3.0 * (np.abs(outs[1][j] - ref[j]) + np.abs(outs[2][j] - ref[j])) for j in range(5)]
+            return (rq, rk + sk, rv, rkb, sq)
+
+        ref = through_stage0(bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm, kbar=kbar_ref))
+        pair = [through_stage0(g_) for g_ in S.perturbed_pair(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm,
+                                                               kbar=kbar_ref, eps=1e-6, seed=r)]
+        allow = S.allowance(ref, pair)
         got = (U.to_np(dq[0, sl]), U.to_np(dk[0, r]), U.to_np(dv[0, r]), U.to_np(dkbar[0, r]), U.to_np(dqbar[0, r]))
         worst = {}
         for j, nm in enumerate(("dq", "dk", "dv", "dkbar", "dqbar")):
-            worst[nm] = rowwise_check(f"learned {nm}[{r}]", got[j].astype(np.float64), ref[j], allow[j], tol)
+            merge(worst, nm, rowwise_check(f"learned {nm}[{r}]", got[j].astype(np.float64), ref[j], allow[j], tol))
         if not per_chunk:
             # one query per kv-head: its gradient is the sum over the chunks
             tot_ref, tot_got = ref[4].sum(axis=0), got[4].astype(np.float64).sum(axis=0)
             assert np.abs(tot_got - tot_ref).max() <= tol * np.abs(tot_ref).max() + allow[4].sum(axis=0).max()
         # the summary path must be a visible part of dk
-        share = np.abs(outs[0][1] - bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm,
+        share = np.abs(ref[1] - bwd.dash_backward_group(qn[0, sl], kn[0, r], vn[0, r], don[0, sl], prm,
                                                             kbar=kbar_ref)[1]).max() / np.abs(ref[1]).max()
         assert share > 0.02, share
-        print(f"learned summaries, kv-head {r}: " + " ".join(f"{a} {b:.2e}" for a, b in worst.items()))
+        print(f"learned summaries, kv-head {r}: {fmt(worst)}")
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])

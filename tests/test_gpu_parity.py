@@ -93,7 +93,7 @@ def test_prefill_with_learned_summaries(name, h_q, h_kv, n, d, block, causal):
     qn = qbar.cpu().numpy().astype(np.float64)
     rep, err = U.check_against_oracle(
         w, q, k, v, run, summaries=lambda b, r, kn: orc.local_attention_summaries(kn, qn[r], block))
-    print(f"{name}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"{name}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
     assert 0.02 < rep.sparsity < 0.98
 
 
@@ -102,7 +102,7 @@ def test_prefill_c1_fp32_full():
     q, k, v = gen(w)
     run = U.run_prefill(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run)
-    print(f"C1: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e} "
+    print(f"C1: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()} "
           f"tau_err {rep.worst_tau_err:.2e} bias_err {rep.worst_bias_err:.2e}")
     assert 0.05 < rep.sparsity < 0.95
 
@@ -144,7 +144,7 @@ def test_prefill_bf16_small(case):
     q, k, v = gen(w)
     run = U.run_prefill(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run)
-    print(f"{name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e} "
+    print(f"{name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()} "
           f"tau_err {rep.worst_tau_err:.2e} bias_err {rep.worst_bias_err:.2e}")
 
 
@@ -159,7 +159,7 @@ def test_prefill_fp32_small(case):
     q, k, v = gen(w)
     run = U.run_prefill(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run)
-    print(f"{name}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"{name}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
 @pytest.mark.parametrize("dtype,causal,n,d,hq,hkv", [("bf16", True, 1000, 128, 8, 2), ("bf16", False, 700, 64, 2, 2),
@@ -190,7 +190,7 @@ def test_decode_small(n_kv, extra):
     q, k, v = gen(w)
     run = U.run_decode(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run)
-    print(f"decode {n_kv}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"decode {n_kv}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
 def test_decode_updates_summary_cache_when_chunk_completes():
@@ -328,19 +328,20 @@ def test_decode_ragged_equals_uniform_decode_at_full_length():
     assert torch.equal(o, ref.o) and torch.equal(lists.mask, ref.lists.mask) and torch.equal(lists.cnt, ref.lists.cnt)
 
 
-def test_stage1_token_ranges_do_not_change_the_result(monkeypatch):
-    """Long prefills run Stage 1 as several launches over token ranges; forcing that on a
-    short sequence must reproduce the single-launch lists bit for bit."""
-    w = Workload("s1_ranges", 2, 8, 2, 1500, 1500, 128, 64, seed=6, window=1)
-    q, k, v = gen(w)
-    monkeypatch.setenv("DASH_S1_SEGS", "1")
-    one = U.run_prefill(w, q, k, v)
-    for segs in ("3", "7"):
-        monkeypatch.setenv("DASH_S1_SEGS", segs)
-        many = U.run_prefill(w, q, k, v)
-        for name in ("mask", "cnt", "idx", "bias", "tau"):
-            assert torch.equal(getattr(one.lists, name), getattr(many.lists, name)), (segs, name)
-        assert torch.equal(one.o, many.o)
+def test_stage1_token_ranges_agree_with_the_oracle_at_their_boundaries():
+    """A causal prefill with 1024 or more chunks runs Stage 1 as four launches over token
+    ranges (cut at multiples of 64 tokens), each with its own row length and rows per
+    workgroup: the rows on both sides of every cut, and the first and last rows, against
+    the oracle."""
+    n = 65536 + 192
+    w = Workload("s1_ranges", 1, 4, 2, n, n, 128, 64, seed=6, window=1)
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    cuts = [((n * s // 4 + 63) // 64) * 64 for s in (1, 2, 3)]
+    rows = [(0, r, i) for r in (0, 1) for c in cuts for i in (c - 64, c - 1, c, c + 1, c + 63)]
+    rows += [(0, r, i) for r in (0, 1) for i in (0, 63, 64, 127, 128, n - 1)]
+    rep, err = U.check_against_oracle(w, q, k, v, run, rows)
+    print(f"token ranges: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
 def test_rising_logits_exercise_the_rescale_path():
@@ -354,7 +355,7 @@ def test_rising_logits_exercise_the_rescale_path():
     q = (q.float() * 3.0).to(q.dtype)
     run = U.run_prefill(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96))
-    print(f"rising prefill: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"rising prefill: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
     o = torch.empty_like(q)
     B.dense_attn(run.params, q, k, v, o, B.alloc_workspace(run.params, DEV))
     torch.cuda.synchronize()
@@ -381,7 +382,7 @@ def test_chunked_prefill_continues_a_longer_cache(dtype, h_q, h_kv, n_q, n_kv, d
     q, k, v = gen(w)
     run = U.run_prefill(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run)
-    print(f"chunked prefill {dtype}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"chunked prefill {dtype}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
     # the same rows as part of a full-length prefill (queries for the earlier positions are arbitrary)
     wf = w.replace(n_q=n_kv)
     qf = torch.zeros((1, h_q, n_kv, d), dtype=q.dtype, device=DEV)
@@ -513,7 +514,7 @@ def test_prefill_mid_sampled(case):
     q, k, v = gen_dev(w)
     run = U.run_prefill(w, q, k, v)
     rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 160))
-    print(f"{name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e} "
+    print(f"{name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()} "
           f"tau_err {rep.worst_tau_err:.2e}")
     assert rep.sparsity > 0.2
 
@@ -523,18 +524,20 @@ def test_prefill_c2_full_size_sampled():
     q, k, v = gen_dev(w)
     run = U.run_prefill(w, q, k, v, want_idx=False)
     rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96, heads=[(0, 0), (0, 5), (0, 7)]))
-    print(f"C2 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"C2 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
-@pytest.mark.parametrize("alpha,offset_sigma", [(1.5, 0.5), (2.0, 1.0), (1.25, 1.0)])
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+@pytest.mark.parametrize("offset_sigma", [0.3, 0.5, 1.0])
 def test_prefill_c4_full_size_sampled(alpha, offset_sigma):
-    """Long prefill (N = 131072, chunks of 128 keys) at three points of the alpha / offset sweep."""
+    """Long prefill (N = 131072, chunks of 128 keys): every point of the alpha / offset sweep,
+    sampled rows of three kv-heads."""
     w = C4.replace(alpha=alpha, offset_sigma=offset_sigma)
     q, k, v = gen_dev(w)
     run = U.run_prefill(w, q, k, v, want_idx=False)
-    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 48, heads=[(0, 1), (0, 6)]))
+    rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 21, heads=[(0, 1), (0, 4), (0, 6)]))
     print(f"C4 alpha={alpha} offset_sigma={offset_sigma}: rows {rep.rows} sparsity {rep.sparsity:.3f} "
-          f"exempt {rep.exempt} out_err {err:.2e}")
+          f"exempt {rep.exempt} {rep.errors()}")
     del run, q, k, v
     torch.cuda.empty_cache()
 
@@ -544,20 +547,26 @@ def test_prefill_c5_full_size_sampled():
     q, k, v = gen_dev(w)
     run = U.run_prefill(w, q, k, v, want_idx=False)
     rep, err = U.check_against_oracle(w, q, k, v, run, U.sample_rows(w, 96, heads=[(0, 0), (1, 9), (3, 15)]))
-    print(f"C5 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"C5 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
-def test_decode_c3_full_size_sampled():
-    w = C3
+@pytest.mark.parametrize("gamma", [1.0, 0.4])
+def test_decode_c3_full_size_sampled(gamma):
+    """The 128k decode step at the temperature of the configuration (93 % chunk sparsity) and at
+    the one that gives the 75 % it names: 32 of the 128 (batch, kv-head) rows against the oracle."""
+    w = C3.replace(gamma=gamma)
     q, k, v = gen_dev(w)
     run = U.run_decode(w, q, k, v)
-    rows = [(b, r, 0) for (b, r) in [(0, 0), (3, 5), (9, 2), (15, 7)]]
+    rows = [(b, (3 * b + j) % w.h_kv, 0) for b in range(w.batch) for j in (0, 4)]
     rep, err = U.check_against_oracle(w, q, k, v, run, rows)
-    print(f"C3 full: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} out_err {err:.2e}")
+    print(f"C3 full gamma={gamma}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
+    assert rep.rows == 32
     # every (batch, kv-head) row: the list is well formed and the output finite
     cnt = run.lists.cnt.cpu().numpy()
     assert cnt.min() >= 1 and cnt.max() <= 2048
     assert torch.isfinite(run.o.float()).all()
+    del run, q, k, v
+    torch.cuda.empty_cache()
 
 
 # ---- Stage 2 on given lists (the kernel-benchmark protocol: randomised masks) ----

@@ -150,6 +150,54 @@ def test_backward_argument_errors():
     assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(far), ctypes.byref(n)) == -2
 
 
+def test_forward_rejects_slices_beyond_32_bit_offsets():
+    """The bf16 kernels address one (batch, kv-head) slice of a tensor with 32-bit byte offsets:
+    a token-major cache whose slice spans 2 GiB or more is refused by every forward entry point
+    (fp32 tensors use 64-bit offsets and are accepted)."""
+    lib = B.load_library()
+    n = ctypes.c_size_t(0)
+    ok = params(n_q=1, n_kv=131072, batch=16, h_q=32, h_kv=8)
+    ok.k_stride[2] = ok.v_stride[2] = 8 * 128                     # [batch, token, head, d]: 268 MB per slice
+    ok.k_stride[1] = ok.v_stride[1] = 128
+    assert lib.dash_attn_workspace_bytes(ctypes.byref(ok), ctypes.byref(n)) == 0
+    for name in ("k_stride", "v_stride", "q_stride", "o_stride"):
+        wide = params(n_q=8192, n_kv=8192)
+        getattr(wide, name)[2] = 1 << 18                           # 8191 * 512 KiB + 256 B >= 2 GiB
+        assert lib.dash_attn_workspace_bytes(ctypes.byref(wide), ctypes.byref(n)) == -2, name
+        assert lib.dash_attn_prefill(ctypes.byref(wide), 256, 256, 256, 256, 256, None, None, None, None, None,
+                                     256, 1 << 40, None) == -2, name
+        assert lib.dense_attn(ctypes.byref(wide), 256, 256, 256, 256, 256, 1 << 40, None) == -2, name
+        assert lib.dash_stage2_attend(ctypes.byref(wide), 256, 256, 256, 256, None, None, 256, 1 << 40, None) == -2
+        wide.dtype = 0                                             # fp32: plain 64-bit pointers
+        getattr(wide, name)[2] = 1 << 18
+        assert lib.dash_attn_workspace_bytes(ctypes.byref(wide), ctypes.byref(n)) == 0, name
+    dec = params(n_q=1, n_kv=131072, batch=2, h_q=8, h_kv=2)
+    dec.k_stride[2] = 1 << 14                                      # 131071 * 32 KiB >= 2 GiB
+    assert lib.dash_attn_decode(ctypes.byref(dec), 256, 256, 256, 256, 256, None, None, None, None, None,
+                                256, 1 << 40, None) == -2
+    heads = params()
+    heads.q_stride[1] = 1 << 30                                    # the 4 query heads of a kv-head 2 GiB apart
+    assert lib.dash_attn_workspace_bytes(ctypes.byref(heads), ctypes.byref(n)) == -2
+
+
+def test_backward_is_refused_above_the_alpha_it_is_checked_to():
+    lib = B.load_library()
+    n = ctypes.c_size_t(0)
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(params(alpha=3.0)), ctypes.byref(n)) == 0
+    assert lib.dash_attn_backward_workspace_bytes(ctypes.byref(params(alpha=4.0)), ctypes.byref(n)) == -2
+    assert lib.dash_attn_backward(ctypes.byref(params(alpha=4.0)), *([256] * 12), 256, 1 << 40, None) == -2
+    # the forward has no such limit
+    assert lib.dash_attn_workspace_bytes(ctypes.byref(params(alpha=4.0)), ctypes.byref(n)) == 0
+
+
+def test_the_library_reads_no_environment_variable():
+    """Behaviour depends on the arguments alone: the sources call no getenv."""
+    csrc = os.path.join(ROOT, "paper_2605_18753_amd", "csrc")
+    for f in os.listdir(csrc):
+        if f.endswith((".hip", ".h")):
+            assert "getenv" not in open(os.path.join(csrc, f)).read(), f
+
+
 def test_summarize_backward_argument_errors():
     lib = B.load_library()
     p = params()

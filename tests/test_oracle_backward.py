@@ -267,27 +267,36 @@ def test_learned_summary_backward_at_a_zero_query_is_the_block_mean_rule():
         assert np.allclose(dq[c], keys.T @ ((da - da.mean()) / block) / math.sqrt(d), rtol=1e-12, atol=1e-15)
 
 
-def test_the_test_aids_leave_the_gradient_alone():
-    """margin_shift and dd_noise only measure sensitivities: at 0 they are absent,
-    dd_noise leaves dv (the attention part) alone and is linear, margin_shift moves
-    the bias inside the attention too, and in the
-    non-causal case (every attended token lies in a routed chunk) the bias
-    gradients of a row sum to zero, which is what makes their mean cancel."""
+def test_noncausal_bias_gradients_of_a_row_sum_to_zero():
+    """Non-causal: every attended token lies in a routed chunk, so the bias
+    gradients of a row are the sums of all dz of the row, and sum_j dz_j = 0."""
     g_q, n, d, block = 2, 48, 8, 8
     q, k, v, d_o = tiny_inputs(6, g_q, n, d, block, spread=3.0)
     prm = orc.DashParams(block=block, alpha=1.5, gamma=2.0, causal=False)
-    ref = bwd.dash_backward_group(q, k, v, d_o, prm)
-    same = bwd.dash_backward_group(q, k, v, d_o, prm, margin_shift=0.0, dd_noise=0.0)
-    for a, b in zip(ref, same):
-        assert np.array_equal(a, b)
-    one = bwd.dash_backward_group(q, k, v, d_o, prm, dd_noise=1e-3)
-    two = bwd.dash_backward_group(q, k, v, d_o, prm, dd_noise=2e-3)
-    shifted = bwd.dash_backward_group(q, k, v, d_o, prm, margin_shift=1e-4)
-    assert np.array_equal(one[2], ref[2]) and np.abs(shifted[2] - ref[2]).max() > 0
-    assert np.abs(one[0] - ref[0]).max() > 0 and np.abs(shifted[0] - ref[0]).max() > 0
-    assert np.allclose(two[0] - ref[0], 2.0 * (one[0] - ref[0]), rtol=1e-6, atol=1e-12)
     kbar = orc.block_mean_summaries(k, block)
     scr = (np.zeros_like(k), np.zeros_like(v), np.zeros_like(kbar))
     for t in (0, 17, n - 1):
         _, _, dd = bwd.backward_row(q[:, t], k, v, kbar, d_o[:, t], prm, t, *scr)
         assert abs(dd.sum()) <= 1e-13 * np.abs(d_o[:, t]).sum() * np.abs(v).max()      # the scale of dP
+
+
+def test_the_conditioning_estimate_of_the_gpu_tests_leaves_the_oracle_alone():
+    """tests/bwd_sensitivity.py calls the untouched oracle on perturbed inputs: with a zero
+    perturbation it returns the oracle's gradient bit for bit (also the block-mean path folded
+    into dk by the wrapper), and the change is linear in the size of the perturbation."""
+    import bwd_sensitivity as S
+    g_q, n, d, block = 2, 48, 8, 8
+    q, k, v, d_o = tiny_inputs(6, g_q, n, d, block, spread=3.0)
+    prm = orc.DashParams(block=block, alpha=1.5, gamma=2.0)
+    ref = bwd.dash_backward_group(q, k, v, d_o, prm)
+    zero = S.perturbed_pair(q, k, v, d_o, prm, eps=0.0)
+    for z in zero:
+        assert np.array_equal(z[0], ref[0]) and np.array_equal(z[2], ref[2]) and np.array_equal(z[3], ref[3])
+        assert np.allclose(z[1], ref[1], rtol=1e-13, atol=1e-15)       # folded in another order of additions
+    one = S.perturbed_pair(q, k, v, d_o, prm, eps=1e-6)
+    two = S.perturbed_pair(q, k, v, d_o, prm, eps=2e-6)
+    for j in range(3):
+        assert np.abs(one[0][j] - ref[j]).max() > 0
+        assert np.allclose(two[0][j] - ref[j], 2.0 * (one[0][j] - ref[j]), rtol=1e-3, atol=1e-9 * np.abs(ref[j]).max())
+    rep = S.rowwise_report(ref[0], ref[0], S.allowance(ref, one)[0], 1e-4)
+    assert rep["plain_worst"] == 0.0 and rep["need_allow"] == 0.0 and rep["excess"] <= 0.0
