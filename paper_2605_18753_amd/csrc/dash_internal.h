@@ -31,23 +31,26 @@ struct Layout {
 // checks that only the Stage-1 router needs (dense attention, size queries).
 int make_layout(const dash_params* p, Layout* L, bool routing = true);
 
-// A kernel that uses more than 64 KB of dynamic LDS has to opt in once per device.  The
-// opt-in is a property of the loaded kernel on that device, not a stream operation, so it
-// is made on the first launch there and recorded (one bit per device ordinal; two threads
-// that race both make the same call).  Nothing else in the library outlives a call.
-struct LdsOptIn { std::atomic<uint64_t> devs{0}; };
+// A kernel that uses a large amount of dynamic LDS (up to the 160 KB of a compute unit) has to opt in, per device, to the size
+// it is launched with.  The opt-in is a property of the loaded kernel on that device, not a
+// stream operation, so it is made when a launch first needs that much there and the size
+// granted is recorded (per device ordinal; two threads that race both make the call, and
+// the larger size wins).  Nothing else in the library outlives a call.
+struct LdsOptIn { std::atomic<uint32_t> granted[64] = {}; };
 inline hipError_t allow_dyn_lds(const void* kern, size_t bytes, LdsOptIn& rec) {
+  if (bytes <= 48 * 1024) return hipSuccess;
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   const bool tracked = dev >= 0 && dev < 64;
-  const uint64_t bit = tracked ? (uint64_t)1 << dev : 0;
-  if (tracked && (rec.devs.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  if (tracked && rec.granted[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
   e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess && tracked) rec.devs.fetch_or(bit, std::memory_order_release);
+  if (e == hipSuccess && tracked) {
+    uint32_t cur = rec.granted[dev].load(std::memory_order_relaxed);
+    while (cur < bytes && !rec.granted[dev].compare_exchange_weak(cur, (uint32_t)bytes, std::memory_order_release)) {}
+  }
   return e;
 }
-constexpr size_t kMaxDynLds = 160 * 1024;   // LDS of one gfx950 compute unit
 
 struct S1Out {
   uint32_t* mask; int32_t* cnt; int32_t* idx; float* bias; float* tau;

@@ -697,9 +697,8 @@ hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const voi
 
 template <auto kern>
 static hipError_t launch_route_k(const S1Args& a, dim3 grid, size_t lds, hipStream_t st) {
-  // the row length of the launch sizes the LDS: opt in to the whole compute unit's once
   static LdsOptIn opt_in;   // one per kernel (kern is a template argument)
-  if (hipError_t e = allow_dyn_lds((const void*)kern, kMaxDynLds, opt_in); e != hipSuccess) return e;
+  if (hipError_t e = allow_dyn_lds((const void*)kern, lds, opt_in); e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, a);
   return hipGetLastError();
 }

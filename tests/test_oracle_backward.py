@@ -278,25 +278,3 @@ def test_noncausal_bias_gradients_of_a_row_sum_to_zero():
     for t in (0, 17, n - 1):
         _, _, dd = bwd.backward_row(q[:, t], k, v, kbar, d_o[:, t], prm, t, *scr)
         assert abs(dd.sum()) <= 1e-13 * np.abs(d_o[:, t]).sum() * np.abs(v).max()      # the scale of dP
-
-
-def test_the_conditioning_estimate_of_the_gpu_tests_leaves_the_oracle_alone():
-    """tests/bwd_sensitivity.py calls the untouched oracle on perturbed inputs: with a zero
-    perturbation it returns the oracle's gradient bit for bit (also the block-mean path folded
-    into dk by the wrapper), and the change is linear in the size of the perturbation."""
-    import bwd_sensitivity as S
-    g_q, n, d, block = 2, 48, 8, 8
-    q, k, v, d_o = tiny_inputs(6, g_q, n, d, block, spread=3.0)
-    prm = orc.DashParams(block=block, alpha=1.5, gamma=2.0)
-    ref = bwd.dash_backward_group(q, k, v, d_o, prm)
-    zero = S.perturbed_pair(q, k, v, d_o, prm, eps=0.0)
-    for z in zero:
-        assert np.array_equal(z[0], ref[0]) and np.array_equal(z[2], ref[2]) and np.array_equal(z[3], ref[3])
-        assert np.allclose(z[1], ref[1], rtol=1e-13, atol=1e-15)       # folded in another order of additions
-    one = S.perturbed_pair(q, k, v, d_o, prm, eps=1e-6)
-    two = S.perturbed_pair(q, k, v, d_o, prm, eps=2e-6)
-    for j in range(3):
-        assert np.abs(one[0][j] - ref[j]).max() > 0
-        assert np.allclose(two[0][j] - ref[j], 2.0 * (one[0][j] - ref[j]), rtol=1e-3, atol=1e-9 * np.abs(ref[j]).max())
-    rep = S.rowwise_report(ref[0], ref[0], S.allowance(ref, one)[0], 1e-4)
-    assert rep["plain_worst"] == 0.0 and rep["need_allow"] == 0.0 and rep["excess"] <= 0.0
