@@ -51,6 +51,7 @@ _SIGNATURES = {
     "dash_stage2_attend": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_attn_prefill": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
     "dash_attn_decode": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
+    "dash_attn_decode_static": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V, _V]),
     "dash_attn_decode_ragged": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_int32, _V, _V, _V, _V, _V, _V, _V,
                                                ctypes.c_size_t, _V]),
     "dense_attn": (ctypes.c_int, [_P, _V, _V, _V, _V, _V, ctypes.c_size_t, _V]),
@@ -215,6 +216,14 @@ def dash_attn_decode(p, q, k_cache, v_cache, kbar_cache, o, lists: Lists, ws: to
                                            _ptr(kbar_cache), _ptr(o), _ptr(lists.mask), _ptr(lists.cnt),
                                            _ptr(lists.idx), _ptr(lists.bias), _ptr(lists.tau), wp, wn,
                                            _stream()), "dash_attn_decode")
+
+
+def dash_attn_decode_static(p, q, k_cache, v_cache, kbar_cache, o, lists: Lists) -> None:
+    """dash_attn_decode on the library's built-in scratch (no workspace, no allocation)."""
+    _check(load_library().dash_attn_decode_static(ctypes.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                                  _ptr(kbar_cache), _ptr(o), _ptr(lists.mask), _ptr(lists.cnt),
+                                                  _ptr(lists.idx), _ptr(lists.bias), _ptr(lists.tau), _stream()),
+           "dash_attn_decode_static")
 
 
 def dash_attn_decode_ragged(p, q, k_cache, v_cache, kbar_cache, seq_lens: torch.Tensor, o, lists: Lists,

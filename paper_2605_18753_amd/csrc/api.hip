@@ -6,7 +6,31 @@
 
 #include "dash_internal.h"
 
+// Scratch for dash_attn_decode_static, the entry point for callers that cannot allocate: one
+// array per GPU the library's code is loaded on, held until the process ends.  In host code the
+// name stands for the symbol, not for a device address: the address is asked for once per device
+// (static_scratch below) and only that pointer is handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace dash {
+
+static std::atomic<void*> g_scratch_ptr[64];   // per device ordinal; nullptr = not asked for yet
+
+// The current device's copy of `scratch`.  Thread-safe (two threads that race both look the
+// address up and store the same value).
+static int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return DASH_ELAUNCH;
+  if (dev < 0 || dev >= 64) return DASH_EUNSUPPORTED;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return DASH_ELAUNCH;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return DASH_OK;
+}
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -245,6 +269,19 @@ int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache, c
                      void* stream) {
   return decode_impl(p, q, k_cache, v_cache, kbar_cache, nullptr, true, o, mask, blk_cnt, blk_idx,
                      blk_bias, tau, workspace, workspace_bytes, stream);
+}
+
+int dash_attn_decode_static(const dash_params* p, const void* q, const void* k_cache, const void* v_cache,
+                            float* kbar_cache, void* o, uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx,
+                            float* blk_bias, float* tau, void* stream) {
+  Layout L;
+  int rc = make_layout(p, &L);
+  if (rc != DASH_OK) return rc;
+  if (L.total > kStaticScratchBytes) return DASH_EWORKSPACE;   // larger than the built-in scratch
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws)) != DASH_OK) return rc;
+  return decode_impl(p, q, k_cache, v_cache, kbar_cache, nullptr, true, o, mask, blk_cnt, blk_idx,
+                     blk_bias, tau, ws, kStaticScratchBytes, stream);
 }
 
 int dash_attn_decode_ragged(const dash_params* p, const void* q, const void* k_cache,
