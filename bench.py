@@ -12,7 +12,8 @@ inputs resident in HBM.  Prints ONE JSON line.
   extras     stage times, speed-up over the in-library dense kernel at the
              config's gamma and at the gamma that gives ~75 % chunk sparsity,
              MFMA flops actually issued, decode step time and HBM rate
-  cpu_baseline  the fp64 oracle timed on a bounded row sample
+  cpu_baseline  the fp64 oracle timed on a bounded row sample, on all host cores
+                (worker processes started before the GPU is touched)
 """
 from __future__ import annotations
 
@@ -27,10 +28,23 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the Stage-2 kernel on the full C2 workload, from the two
-# rocprofv3 --pmc runs summarised in profiles/bench_c2_c3_hbm_traffic.md
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0).  Not measurable from inside this script.
-S2_TRAFFIC_BYTES_C2 = 2.539e9 + 0.388e9
+# HBM bytes per launch of the Stage-2 kernel on the headline workload cannot be measured from
+# inside this script: they come from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) whose
+# summary is committed in this file, which carries one line `traffic_json: {...}` per kernel
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "prefill_c2_hbm_traffic.md")
+
+
+def traffic_from_profile(kernel, workload):
+    """Scaled FETCH_SIZE + WRITE_SIZE bytes per launch from the committed summary, or None."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("traffic_json:"):
+                rec = json.loads(line[len("traffic_json:"):])
+                if rec.get("kernel") == kernel and rec.get("workload") == workload:
+                    return float(rec["fetch_bytes"]) + float(rec["write_bytes"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
 
 
 def parse():
@@ -41,6 +55,10 @@ def parse():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the nine-point 128k sweep")
+    ap.add_argument("--only", default=None, choices=["c2-gamma1", "c2-gamma1.5", "c3-gamma1", "c3-gamma0.4"],
+                    help="run one workload at one temperature and nothing else (profiling runs: the per-kernel "
+                         "figures of a rocprofv3 run then belong to that configuration alone)")
     ap.add_argument("--backward-only", action="store_true",
                     help="time only the forward + backward of the training-shaped workload and print its JSON line "
                          "(the command of the backward kernels' rocprofv3 summaries)")
@@ -111,7 +129,7 @@ def prefill_stats(w, lists, torch):
     return dict(f_alg=f_alg, f_exec=f_exec, f_dense=f_dense, sparsity=sparsity)
 
 
-def bench_prefill(w, steps, warmup, torch, B, make_inputs):
+def bench_prefill(w, steps, warmup, torch, B, make_inputs, sensors=None):
     dev = "cuda:0"
     q, k, v = make_inputs(w, dev)
     o = torch.empty_like(q)
@@ -129,10 +147,17 @@ def bench_prefill(w, steps, warmup, torch, B, make_inputs):
     kbar_l = torch.empty_like(kbar)
     t_s0l = timed(lambda: B.dash_kbar_summarize(p, k, qbar, kbar_l), steps, 1, torch)
     t_s1 = timed(lambda: B.dash_stage1_route(p, q, kbar, lists, ws), steps, 1, torch)
-    t_s2 = timed(lambda: B.dash_stage2_attend(p, q, k, v, o, lists, ws), steps, 1, torch)
     od = torch.empty_like(q)
-    t_dense = timed(lambda: B.dense_attn(p, q, k, v, od, ws), steps, warmup, torch)
-    res = dict(ms_step=t_all, ms_stage0=t_s0, ms_stage0_learned=t_s0l, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
+    if sensors is None:
+        t_s2 = timed(lambda: B.dash_stage2_attend(p, q, k, v, o, lists, ws), steps, 1, torch)
+        t_dense = timed(lambda: B.dense_attn(p, q, k, v, od, ws), steps, warmup, torch)
+        sens = None
+    else:
+        # the box's clock / power readings while each of the two Stage-2 kernels runs alone
+        t_s2, sn_s2 = sensors.during(lambda: timed(lambda: B.dash_stage2_attend(p, q, k, v, o, lists, ws), steps, 1, torch))
+        t_dense, sn_d = sensors.during(lambda: timed(lambda: B.dense_attn(p, q, k, v, od, ws), steps, warmup, torch))
+        sens = {"stage2_loop": sn_s2, "dense_loop": sn_d}
+    res = dict(sensors=sens, ms_step=t_all, ms_stage0=t_s0, ms_stage0_learned=t_s0l, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
     del q, k, v, o, od, ws, lists, kbar, kbar_l
     torch.cuda.empty_cache()
     return res
@@ -211,7 +236,7 @@ def bench_decode(w, steps, warmup, torch, B, make_inputs):
 
 def paper_protocol(steps, warmup, torch, B):
     """Stage-2 speed-up over the in-library dense attention on the shapes and the
-    randomised masks of the paper's kernel benchmark (Sec. 5.3, App. B.3, Table 5).
+    randomised masks of the paper's kernel benchmark (Sec. 5.2, App. B.2, Table 5).
     Stage 0/1 do not depend on the mask; their time on the same tensors is given
     beside it so that the speed-up can be read with and without routing."""
     from paper_2605_18753_amd.inputs import random_chunk_lists
@@ -294,35 +319,201 @@ def gemm_context(torch):
     return out
 
 
-def cpu_baseline(w, seconds, torch, make_inputs):
-    """The oracle as it stands, single thread, on a uniform sample of query rows of
-    the same workload; reported in the metric's unit (dense-equivalent flops / s)."""
+# ---- the oracle on the host cores -------------------------------------------------------
+# Worker processes are forked before this process touches the GPU (a fork afterwards would
+# duplicate a live GPU context).  Each worker holds one kv-head's worth of the workload's
+# tensors (inherited through the fork), runs oracle rows drawn uniformly until its deadline
+# and reports rows and dense-equivalent flops.
+_ORC = {}
+
+
+def _orc_worker(args):
+    name, seconds, seed = args
     import numpy as np
     from oracle import dash_oracle as orc
     try:
         from threadpoolctl import threadpool_limits
-        limiter = threadpool_limits(limits=1)
+        threadpool_limits(limits=1)
     except Exception:  # pragma: no cover
-        limiter = None
-    ws = w.replace(batch=1, h_q=w.g_q, h_kv=1)       # one kv-head's worth of tensors
-    q, k, v = make_inputs(ws, "cpu")
-    qn, kn, vn = (t.float().numpy() for t in (q, k, v))
-    prm = orc.DashParams(block=w.block, alpha=w.alpha, gamma=w.gamma, sigma=w.sigma, causal=w.causal)
-    kbar = orc.block_mean_summaries(kn, w.block)
-    rng = np.random.default_rng(0)
+        pass
+    w, qn, kn, vn, kbar, prm, rows_of = _ORC[name]
+    rng = np.random.default_rng(seed)
     t0 = time.perf_counter()
     flops, rows = 0.0, 0
     while time.perf_counter() - t0 < seconds:
-        i = int(rng.integers(0, w.n_q))
+        i = int(rng.integers(rows_of[0], rows_of[1]))
         orc.dash_row(qn, kn, vn, kbar, prm, 0, 0, i)
-        flops += 4.0 * w.head_dim * w.g_q * (i + 1)
+        pos = w.n_kv - w.n_q + i
+        flops += 4.0 * w.head_dim * w.g_q * ((pos + 1) if w.causal else w.n_kv)
         rows += 1
-    dt = time.perf_counter() - t0
-    if limiter is not None:
-        limiter.restore_original_limits() if hasattr(limiter, "restore_original_limits") else None
-    return dict(value=flops / dt / 1e12, unit="TFLOP/s", cores=1, kind="oracle",
-                sample=f"{rows} uniformly drawn query rows (all {w.g_q} heads of one kv-head) of the same "
-                       f"workload, {dt:.1f} s, numpy fp64, 1 thread; dense-equivalent flops of those rows / time")
+    return rows, flops, time.perf_counter() - t0
+
+
+def host_cores():
+    # a one-GPU machine gives this job 16 cores whatever os.cpu_count() shows
+    return max(1, min(16, os.cpu_count() or 1))
+
+
+def oracle_on_host(workloads, seconds):
+    """Times the oracle as it stands (numpy fp64, one row at a time) on all host cores for
+    every workload in `workloads` (name -> Workload), `seconds` of wall time each.  Returns
+    name -> dict(rows_per_s, flops_per_s, rows, cores, seconds)."""
+    import multiprocessing as mp
+    import numpy as np
+    from oracle import dash_oracle as orc
+    from paper_2605_18753_amd.inputs import make_inputs
+    cores = host_cores()
+    for name, w in workloads.items():
+        ws = w.replace(batch=1, h_q=w.g_q, h_kv=1)       # one kv-head's worth of tensors
+        q, k, v = make_inputs(ws, "cpu")
+        qn, kn, vn = (t.float().numpy() for t in (q, k, v))
+        prm = orc.DashParams(block=w.block, alpha=w.alpha, gamma=w.gamma, sigma=w.sigma, causal=w.causal)
+        _ORC[name] = (ws, qn, kn, vn, orc.block_mean_summaries(kn, w.block), prm, (0, ws.n_q))
+    out = {}
+    ctx = mp.get_context("fork")
+    with ctx.Pool(cores) as pool:
+        for name in workloads:
+            res = pool.map(_orc_worker, [(name, seconds, 1000 + c) for c in range(cores)])
+            rows = sum(r[0] for r in res)
+            dt = max(r[2] for r in res)
+            out[name] = dict(rows=rows, cores=cores, seconds=dt, rows_per_s=rows / dt,
+                             flops_per_s=sum(r[1] for r in res) / dt)
+    _ORC.clear()
+    return out
+
+
+def cpu_baseline(w, orc_res):
+    r = orc_res[w.name]
+    return dict(value=r["flops_per_s"] / 1e12, unit="TFLOP/s", cores=r["cores"], kind="oracle",
+                sample=f"{r['rows']} uniformly drawn query rows (all {w.g_q} heads of one kv-head) of the same "
+                       f"workload in {r['seconds']:.1f} s on {r['cores']} worker processes (numpy fp64, one thread "
+                       f"each); dense-equivalent flops of those rows / wall time")
+
+
+# ---- what the box reports while a kernel runs ------------------------------------------------
+class Sensors:
+    """Samples the GPU's engine clock and power from sysfs (hwmon) in a thread while a timing
+    loop runs; fields are None where the box does not expose them to this user."""
+
+    def __init__(self):
+        import glob
+        self.freq = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/freq1_input"))
+        self.dpm = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.power = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average") +
+                            glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+
+    @staticmethod
+    def _read(path):
+        try:
+            return float(open(path).read().split()[0])
+        except (OSError, ValueError, IndexError):
+            return None
+
+    @staticmethod
+    def _dpm_mhz(path):
+        """The level marked current ('*') in a pp_dpm_sclk listing such as '1: 2100Mhz *'."""
+        try:
+            for line in open(path):
+                if "*" in line:
+                    return float(line.split(":")[1].lower().split("mhz")[0])
+        except (OSError, ValueError, IndexError):
+            pass
+        return None
+
+    def during(self, fn):
+        """Runs fn() while sampling every 2 ms; returns (fn's result, summary dict)."""
+        import threading
+        f, pw, stop = [], [], threading.Event()
+
+        def loop():
+            while not stop.is_set():
+                if self.freq:
+                    x = self._read(self.freq[0])
+                    if x:
+                        f.append(x / 1e6)            # Hz -> MHz
+                elif self.dpm:
+                    x = self._dpm_mhz(self.dpm[0])
+                    if x:
+                        f.append(x)
+                if self.power:
+                    x = self._read(self.power[0])
+                    if x:
+                        pw.append(x / 1e6)           # microwatt -> W
+                time.sleep(0.002)
+
+        th = threading.Thread(target=loop, daemon=True)
+        th.start()
+        try:
+            res = fn()
+        finally:
+            stop.set()
+            th.join()
+        mean = lambda xs: sum(xs) / len(xs) if xs else None
+        return res, {"sclk_mhz_mean": mean(f), "sclk_mhz_min": min(f) if f else None, "power_w_mean": mean(pw),
+                     "samples": max(len(f), len(pw))}
+
+
+def microbench(torch, steps):
+    """Achievable rates on this machine: streaming read of 4 GiB of HBM, and a register-fed loop of
+    v_mfma_f32_32x32x16_bf16 (8 independent accumulators per wave, 2 workgroups of 4 waves per
+    CU) on operands that toggle and on constant ones.  Kernels: csrc/microbench.hip."""
+    import ctypes
+    from paper_2605_18753_amd.build import MICROBENCH_LIB
+    if not os.path.exists(MICROBENCH_LIB):
+        return None
+    lib = ctypes.CDLL(MICROBENCH_LIB)
+    lib.dash_mb_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    lib.dash_mb_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    nbytes = 4 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    ms = timed(lambda: lib.dash_mb_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), st), max(steps, 5), 2, torch)
+    out = {"stream_read_GBps": nbytes / (ms * 1e-3) / 1e9}
+    del src
+    torch.cuda.empty_cache()
+    sens = Sensors()
+    flops = ctypes.c_double(0.0)
+    for name, rnd in (("random_operands", 1), ("constant_operands", 0)):
+        fn = lambda: lib.dash_mb_mfma_loop(sink.data_ptr(), 512, 20000, rnd, ctypes.byref(flops), st)
+        ms, sn = sens.during(lambda: timed(fn, 3, 1, torch))
+        out[f"mfma_loop_tflops_{name}"] = flops.value / (ms * 1e-3) / 1e12
+        out[f"mfma_loop_sensors_{name}"] = sn
+    return out
+
+
+def c4_sweep(torch, B, make_inputs, C4, small):
+    """The long-prefill configuration at its nine (alpha, key-offset sigma) points: time of the
+    whole prefill and of the dense kernel, chunk sparsity, algorithmic / executed flops."""
+    rows = []
+    for alpha in (1.25, 1.5, 2.0):
+        for off in (0.3, 0.5, 1.0):
+            w = C4.replace(alpha=alpha, offset_sigma=off)
+            if small:
+                w = w.replace(n_q=8192, n_kv=8192, name="C4_small")
+            r = bench_prefill(w, 2, 1, torch, B, make_inputs)
+            rows.append({"alpha": alpha, "offset_sigma": off, "chunk_sparsity": r["sparsity"],
+                         "ms_step": r["ms_step"], "ms_stage1": r["ms_stage1"], "ms_stage2": r["ms_stage2"],
+                         "ms_dense": r["ms_dense"], "speedup_vs_dense": r["ms_dense"] / r["ms_step"],
+                         "f_alg_over_f_exec": r["f_alg"] / r["f_exec"],
+                         "effective_tflops": r["f_dense"] / (r["ms_step"] * 1e-3) / 1e12,
+                         "stage2_alg_mfma_frac": r["f_alg"] / (r["ms_stage2"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS})
+    return rows
+
+
+def c1_time(torch, B, make_inputs, C1, steps):
+    """The fp32 single-head non-causal configuration (a correctness configuration: time only)."""
+    dev = "cuda:0"
+    q, k, v = make_inputs(C1, dev)
+    o = torch.empty_like(q)
+    p = B.make_params(q, k, v, o, C1.block, C1.alpha, C1.gamma, C1.sigma, C1.causal)
+    kbar = torch.empty(B.kbar_shape(p), dtype=torch.float32, device=dev)
+    lists = B.Lists.allocate(p, dev, idx=False, tau=False)
+    ws = B.alloc_workspace(p, dev)
+    t = timed(lambda: B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws), max(steps, 20), 3, torch)
+    td = timed(lambda: B.dense_attn(p, q, k, v, o, ws), max(steps, 20), 3, torch)
+    return {"workload": C1.name, "us_prefill": t * 1e3, "us_dense": td * 1e3}
 
 
 def main():
@@ -332,15 +523,32 @@ def main():
         sys.exit(2)
     import torch
     from paper_2605_18753_amd import binding as B
-    from paper_2605_18753_amd.inputs import C2, C3, C5, make_inputs
+    from paper_2605_18753_amd.inputs import C1, C2, C3, C4, C5, make_inputs
     B.load_library()
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = C2
     wd = C3
     if a.small:
         w = w.replace(n_q=4096, n_kv=4096, name="C2_small")
         wd = wd.replace(n_kv=16384, batch=4, name="C3_small")
+    full_run = not (a.paper_protocol or a.backward_only or a.only)
+    # the oracle on the host cores first: its worker processes are forked before the GPU is touched
+    orc_res = None
+    if full_run and not a.no_cpu:
+        others = {} if a.small else {"C1": C1, "C3": wd, "C4": C4.replace(alpha=1.5, offset_sigma=0.5), "C5": C5}
+        orc_res = oracle_on_host({w.name: w}, a.cpu_seconds)
+        orc_res.update(oracle_on_host(others, min(3.0, a.cpu_seconds)))
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
 
+    if a.only:
+        g_ = float(a.only.split("gamma")[1])
+        if a.only.startswith("c2"):
+            r = bench_prefill(w.replace(gamma=g_), a.steps, a.warmup, torch, B, make_inputs)
+            r = {k_: r[k_] for k_ in ("ms_step", "ms_stage0", "ms_stage1", "ms_stage2", "ms_dense", "sparsity")}
+        else:
+            r = bench_decode(wd.replace(gamma=g_), max(a.steps, 20), a.warmup, torch, B, make_inputs)
+            r = {k_: r[k_] for k_ in ("us_step", "us_dense", "sparsity", "kv_gbs")}
+        print(json.dumps({"only": a.only, "steps": a.steps, **r}))
+        return
     if a.paper_protocol:
         res = paper_protocol(a.steps, a.warmup, torch, B)
         print(json.dumps({"metric": "Stage-2 speed-up over the in-library dense attention, randomised chunk masks "
@@ -365,17 +573,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-    main_res = bench_prefill(w, a.steps, a.warmup, torch, B, make_inputs)
+    sens = Sensors()
+    main_res = bench_prefill(w, a.steps, a.warmup, torch, B, make_inputs, sensors=sens)
+    sens_main = main_res["sensors"]
     # the gamma that lands near 75 % chunk sparsity on this generator
     w75 = w.replace(gamma=1.5)
     res75 = bench_prefill(w75, a.steps, a.warmup, torch, B, make_inputs)
+    sweep = None if a.no_sweep else c4_sweep(torch, B, make_inputs, C4, a.small)
+    c1 = c1_time(torch, B, make_inputs, C1, a.steps)
+    mb = None if a.small else microbench(torch, a.steps)
     dec = None
     if not a.no_decode:
         dec = dict(gamma1=bench_decode(wd, max(a.steps, 20), a.warmup, torch, B, make_inputs),
                    gamma04=bench_decode(wd.replace(gamma=0.4), max(a.steps, 20), a.warmup, torch, B, make_inputs))
     wb = C5.replace(n_q=2048, n_kv=2048, batch=1, name="C5_small") if a.small else C5
     bwd = None if a.no_backward else bench_backward(wb, a.steps, a.warmup, torch, B, make_inputs)
-    cpu = None if a.no_cpu else cpu_baseline(w, a.cpu_seconds, torch, make_inputs)
+    cpu = None if orc_res is None else cpu_baseline(w, orc_res)
     gemm = None if a.small else gemm_context(torch)
 
     def tf(flops, ms):
@@ -395,7 +608,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "s2_attend_kernel<128,false>",
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None if a.small else S2_TRAFFIC_BYTES_C2},
+                     "traffic": None if a.small else traffic_from_profile("s2_attend_kernel<128,false>", "C2 gamma=1"),
+                     "traffic_source": os.path.relpath(TRAFFIC_PROFILE, ROOT)},
         "cpu_baseline": cpu,
         "extras": {
             "chunk_sparsity": main_res["sparsity"],
@@ -413,6 +627,17 @@ def main():
             "stage2_exec_mfma_frac": tf(main_res["f_exec"], main_res["ms_stage2"]) / MFMA_BF16_PEAK_TFLOPS,
             "f_alg_over_f_exec": main_res["f_alg"] / main_res["f_exec"],
             "library_gemm_bf16_tflops": gemm,
+            # achievable rates on this machine (csrc/microbench.hip) and what its sensors report during the
+            # headline prefill loop (engine clock, power): context for the MFMA / HBM fractions
+            "microbench": mb,
+            "sensors": sens_main,
+            "C1_fp32_single_head": c1,
+            "C4_sweep_128k": sweep,
+            # the oracle on the host cores for the other configurations: rows per second on a 3 s sample and
+            # the whole configuration's time extrapolated from it (rows are independent)
+            "oracle_on_host": None if orc_res is None else {
+                name: {"rows_per_s": r["rows_per_s"], "cores": r["cores"], "sample_rows": r["rows"],
+                       "sample_seconds": r["seconds"]} for name, r in orc_res.items()},
             "at_75pct_sparsity": {
                 "gamma": w75.gamma, "chunk_sparsity": res75["sparsity"],
                 "effective_tflops": tf(res75["f_dense"], res75["ms_step"]),

@@ -8,6 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdash_attn.so")
+# bench.py's yardstick kernels (streaming read, register-fed MFMA loop): their own small library
+MICROBENCH_LIB = os.path.join(HERE, "libdash_microbench.so")
 SOURCES = ["api.hip", "compress.hip", "stage1.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip", "backward.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -31,6 +33,11 @@ def build(verbose: bool = True, lib: str = LIB, extra=()) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    if lib == LIB:
+        cmd = [hipcc, *FLAGS, *extra, os.path.join(CSRC, "microbench.hip"), "-o", MICROBENCH_LIB]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return lib
 
 

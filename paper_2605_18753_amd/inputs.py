@@ -149,7 +149,7 @@ def shrink(w: Workload, *, n: Optional[int] = None, batch: Optional[int] = None,
 def random_chunk_lists(batch: int, h_kv: int, n_q: int, n_kv: int, block: int, sparsity: float,
                        device="cpu", seed: int = 0, bias_sigma: float = 0.0):
     """Randomised attended-chunk lists in the Stage-1 output format, the stand-in
-    for the kernel benchmark of the paper (App. B.3: the Stage-2 block mask is
+    for the kernel benchmark of the paper (App. B.2: the Stage-2 block mask is
     randomised to a target sparsity).  Query t sits at position n_kv - n_q + t;
     every complete chunk before its own is kept independently with probability
     1 - sparsity, its own (diagonal) chunk always.  Returns (mask int32
