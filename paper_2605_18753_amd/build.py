@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdash_attn.so")
 # bench.py's yardstick kernels (streaming read, register-fed MFMA loop): their own small library
 MICROBENCH_LIB = os.path.join(HERE, "libdash_microbench.so")
-SOURCES = ["api.hip", "compress.hip", "stage1.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip", "backward.hip"]
+SOURCES = ["api.hip", "compress.hip", "stage1.hip", "stage1_regs.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip", "backward.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -25,44 +25,13 @@
 
 #include "common.h"
 #include "dash_internal.h"
+#include "stage1_common.h"
 
 namespace dash {
 
-struct S1Args {
-  const void* q;
-  const uint16_t* ksplit;
-  const float* scores;
-  uint32_t* mask;
-  int32_t* cnt;
-  int32_t* idx;
-  float* bias;
-  float* tau;
-  int batch, h_q, h_kv, g_q, n_q, n_kv, block, t_c, t_all, words, pos0, causal, window, ld;
-  const int32_t* seq_lens;   // decode with per-sequence lengths (device, [batch]) or null
-  int tok_base, tok_end;     // this launch covers query tokens [tok_base, tok_end) of every sequence
-  int64_t qs_b, qs_h, qs_t;
-  float xscale, pexp, alpha, inv_sigma;
-};
-
-enum { MODE_P1 = 0, MODE_P2 = 1, MODE_P4 = 2, MODE_GEN = 3, MODE_BISECT = 4 };
-
-// u^p and u^(p-1) for u >= 0 (0 -> 0, and 0 for the derivative term as well)
-template <int MODE>
-__device__ __forceinline__ void pow_terms(float u, float p, float& f, float& g) {
-  if constexpr (MODE == MODE_P1) {
-    f = u; g = u > 0.f ? 1.f : 0.f;
-  } else if constexpr (MODE == MODE_P2) {
-    f = u * u; g = u;
-  } else if constexpr (MODE == MODE_P4) {
-    const float u2 = u * u; g = u2 * u; f = u2 * u2;
-  } else {
-    g = u > 0.f ? exp2f((p - 1.f) * log2f(u)) : 0.f;
-    f = g * u;
-  }
-}
-template <int MODE> __device__ __forceinline__ float pow_p(float u, float p) {
-  float f, g; pow_terms<MODE>(u, p, f, g); return f;
-}
+// stage1_regs.hip
+bool s1_regs_applicable(const dash_params& p, const Layout& L, int max_cand);
+hipError_t launch_s1_regs(const dash_params& p, const Layout& L, const S1Args& a, hipStream_t st);
 
 // Solve RB rows at once (interleaved for ILP).  Row values live in registers:
 // lane l holds chunks l, l+64, ...  On exit the rows of S hold the per-head
@@ -762,6 +731,11 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
     }
     a.ld = ((max_cand + 15) / 16) * 16 + 4;
     a.tok_base = t0; a.tok_end = t1;
+    if (mfma && s1_regs_applicable(p, L, max_cand)) {
+      // short rows, small GQA groups: the score rows stay in registers (stage1_regs.hip)
+      if (hipError_t e = launch_s1_regs(p, L, a, st); e != hipSuccess) return e;
+      continue;
+    }
     int mt = 1;
     if (mfma) {
       if ((size_t)64 * a.ld * 4 <= 65536) mt = 4;
