@@ -10,7 +10,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdash_attn.so")
 # bench.py's yardstick kernels (streaming read, register-fed MFMA loop): their own small library
 MICROBENCH_LIB = os.path.join(HERE, "libdash_microbench.so")
-SOURCES = ["api.hip", "compress.hip", "stage1.hip", "stage1_regs.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip", "backward.hip"]
+# (source, extra defines, object name); stage1_regs.hip is compiled once per GQA group size
+SOURCES = [(s, [], s.replace(".hip", ".o")) for s in
+           ["api.hip", "compress.hip", "stage1.hip", "stage2.hip", "stage2_decode.hip", "stage2_f32.hip", "backward.hip"]]
+SOURCES += [("stage1_regs.hip", [f"-DDASH_S1R_G={g}"], f"stage1_regs_g{g}.o") for g in (1, 2, 4, 8, 16)]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-w",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -19,9 +22,9 @@ def build(verbose: bool = True, lib: str = LIB, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     extra = list(extra) + os.environ.get("DASH_EXTRA_FLAGS", "").split()
     objs, procs = [], []
-    for s in SOURCES:   # one compiler process per source file, all at once
-        o = os.path.join(CSRC, s.replace(".hip", ".o"))
-        cmd = [hipcc, *[f for f in FLAGS if f != "-shared"], *extra, "-c", os.path.join(CSRC, s), "-o", o]
+    for s, defs, oname in SOURCES:   # one compiler process per object file, all at once
+        o = os.path.join(CSRC, oname)
+        cmd = [hipcc, *[f for f in FLAGS if f != "-shared"], *extra, *defs, "-c", os.path.join(CSRC, s), "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd)))

@@ -29,9 +29,29 @@
 
 namespace dash {
 
-// stage1_regs.hip
-bool s1_regs_applicable(const dash_params& p, const Layout& L, int max_cand);
-hipError_t launch_s1_regs(const dash_params& p, const Layout& L, const S1Args& a, hipStream_t st);
+// Whether a token range whose longest row has max_cand candidates goes to the
+// register-resident kernels (stage1_regs.hip): bf16 prefill, rows of up to 512 chunks, or
+// up to 1536 at head dimension 128.
+static bool s1_regs_applicable(const dash_params& p, const Layout& L, int max_cand) {
+  if (!L.use_mfma || L.seq_lens) return false;
+  return max_cand <= 512 || (max_cand <= 1536 && p.head_dim == 128);
+}
+
+static hipError_t launch_s1_regs(const dash_params& p, const Layout& L, const S1Args& a, int max_cand, hipStream_t st) {
+  int mode;
+  if (a.pexp < 1.f) mode = MODE_BISECT;
+  else if (a.pexp == 1.f) mode = MODE_P1;
+  else if (a.pexp == 2.f) mode = MODE_P2;
+  else if (a.pexp == 4.f) mode = MODE_P4;
+  else mode = MODE_GEN;
+  switch (L.g_q) {
+    case 1: return launch_s1_regs_g1(a, p.head_dim, mode, max_cand, st);
+    case 2: return launch_s1_regs_g2(a, p.head_dim, mode, max_cand, st);
+    case 4: return launch_s1_regs_g4(a, p.head_dim, mode, max_cand, st);
+    case 8: return launch_s1_regs_g8(a, p.head_dim, mode, max_cand, st);
+    default: return launch_s1_regs_g16(a, p.head_dim, mode, max_cand, st);
+  }
+}
 
 // Solve RB rows at once (interleaved for ILP).  Row values live in registers:
 // lane l holds chunks l, l+64, ...  On exit the rows of S hold the per-head
@@ -711,17 +731,42 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
   a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
   a.xscale = L.xscale; a.pexp = L.pexp; a.alpha = p.alpha; a.inv_sigma = 1.f / p.sigma;
   const bool mfma = L.use_mfma && ksplit != nullptr;
-  // A workgroup keeps the score rows of its tokens in LDS, sized for the longest row
-  // of the launch.  Causal rows grow with the position, so a long prefill is cut into
-  // token ranges (boundaries at multiples of 64 tokens, longest range first), each
-  // launched with the row length, rows per workgroup and LDS size of its own longest
-  // row: the early ranges get more rows per workgroup (fewer re-reads of the summaries)
-  // and more workgroups per CU.  Measured: 96k tokens, GQA group 16: 25.9 -> 17.9 ms;
-  // 128k tokens, chunk 128: 12.5 -> 11.0 ms; no effect at 512 chunks or fewer.
-  const int nseg = (p.causal && L.t_c >= 1024 && p.n_q > 1 && !L.seq_lens) ? 4 : 1;
-  for (int sg = nseg - 1; sg >= 0; sg--) {
-    const int t0 = (int)(((int64_t)p.n_q * sg / nseg + 63) / 64 * 64);
-    const int t1 = sg == nseg - 1 ? p.n_q : (int)(((int64_t)p.n_q * (sg + 1) / nseg + 63) / 64 * 64);
+  // Token ranges, each launched with the kernel and the sizes that fit its longest row
+  // (causal rows grow with the position; boundaries at multiples of 64 tokens, longest
+  // range first).  The register-resident kernels take the tokens whose rows have up to
+  // 512 candidates, and those with up to 1536 (head dimension 128), as one range each.
+  // What is left goes to the kernel below, which keeps the score rows of a workgroup in
+  // LDS, sized for the longest row of its launch: there a long prefill is cut into four
+  // ranges, so that the early ones get more rows per workgroup (fewer re-reads of the
+  // summaries) and more workgroups per CU.  Measured with that kernel alone: 96k tokens,
+  // GQA group 16: 25.9 -> 17.9 ms; 128k tokens, chunk 128: 12.5 -> 11.0 ms.
+  int bounds[8];
+  int nb = 0;
+  bounds[nb++] = 0;
+  if (p.causal && p.n_q > 1 && !L.seq_lens) {
+    // the first token whose row has more than `cap` candidates
+    auto first_beyond = [&](int cap) {
+      const int64_t t = (int64_t)(cap + 1 + p.window) * p.block_size - L.pos0;
+      return (int)(t < 0 ? 0 : (t > p.n_q ? p.n_q : t));
+    };
+    int lds_from = 0;   // tokens from here on go to the LDS-row kernel
+    if (mfma) {
+      const int t512 = first_beyond(512);
+      const int t1536 = p.head_dim == 128 ? first_beyond(1536) : t512;
+      if (t512 > 0 && t512 < p.n_q) bounds[nb++] = t512;
+      if (t1536 > t512 && t1536 < p.n_q) bounds[nb++] = t1536;
+      lds_from = t1536;
+    }
+    if (L.t_c >= 1024 && lds_from < p.n_q) {
+      for (int sg = 1; sg < 4; sg++) {
+        const int t = (int)((lds_from + (int64_t)(p.n_q - lds_from) * sg / 4 + 63) / 64 * 64);
+        if (t > bounds[nb - 1] && t < p.n_q) bounds[nb++] = t;
+      }
+    }
+  }
+  bounds[nb] = p.n_q;
+  for (int sg = nb - 1; sg >= 0; sg--) {
+    const int t0 = bounds[sg], t1 = bounds[sg + 1];
     if (t1 <= t0) continue;
     int max_cand = L.t_c;
     if (p.causal && !L.seq_lens) {
@@ -732,8 +777,8 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
     a.ld = ((max_cand + 15) / 16) * 16 + 4;
     a.tok_base = t0; a.tok_end = t1;
     if (mfma && s1_regs_applicable(p, L, max_cand)) {
-      // short rows, small GQA groups: the score rows stay in registers (stage1_regs.hip)
-      if (hipError_t e = launch_s1_regs(p, L, a, st); e != hipSuccess) return e;
+      // the score rows stay in registers (stage1_regs.hip)
+      if (hipError_t e = launch_s1_regs(p, L, a, max_cand, st); e != hipSuccess) return e;
       continue;
     }
     int mt = 1;

@@ -41,4 +41,11 @@ template <int MODE> __device__ __forceinline__ float pow_p(float u, float p) {
   float f, g; pow_terms<MODE>(u, p, f, g); return f;
 }
 
+// The register-resident Stage 1 (stage1_regs.hip), one object file per GQA group size.
+hipError_t launch_s1_regs_g1(const S1Args& a, int head_dim, int mode, int max_cand, hipStream_t st);
+hipError_t launch_s1_regs_g2(const S1Args& a, int head_dim, int mode, int max_cand, hipStream_t st);
+hipError_t launch_s1_regs_g4(const S1Args& a, int head_dim, int mode, int max_cand, hipStream_t st);
+hipError_t launch_s1_regs_g8(const S1Args& a, int head_dim, int mode, int max_cand, hipStream_t st);
+hipError_t launch_s1_regs_g16(const S1Args& a, int head_dim, int mode, int max_cand, hipStream_t st);
+
 }  // namespace dash

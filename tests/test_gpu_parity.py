@@ -328,20 +328,25 @@ def test_decode_ragged_equals_uniform_decode_at_full_length():
     assert torch.equal(o, ref.o) and torch.equal(lists.mask, ref.lists.mask) and torch.equal(lists.cnt, ref.lists.cnt)
 
 
-def test_stage1_token_ranges_agree_with_the_oracle_at_their_boundaries():
-    """A causal prefill with 1024 or more chunks runs Stage 1 as four launches over token
-    ranges (cut at multiples of 64 tokens), each with its own row length and rows per
-    workgroup: the rows on both sides of every cut, and the first and last rows, against
-    the oracle."""
-    n = 65536 + 192
-    w = Workload("s1_ranges", 1, 4, 2, n, n, 128, 64, seed=6, window=1)
+@pytest.mark.parametrize("name,h_q,h_kv,n,window", [
+    ("g2_1027_chunks", 4, 2, 65536 + 192, 1),      # rows of up to 512 chunks, then of up to 1536
+    ("g16_1538_chunks", 16, 1, 98304 + 128, 0),    # ... and a last range beyond 1536 chunks
+    ("g8_781_chunks", 8, 1, 50000, 2),
+])
+def test_stage1_token_ranges_agree_with_the_oracle_at_their_boundaries(name, h_q, h_kv, n, window):
+    """A long causal bf16 prefill runs Stage 1 as several launches over token ranges, cut where
+    the row length passes 512 and 1536 candidate chunks (each range has its own kernel: whole
+    rows per wave, rows split over a wave pair, rows in LDS): the rows on both sides of every
+    cut, rows inside every range, and the first and last rows, against the oracle."""
+    w = Workload(name, 1, h_q, h_kv, n, n, 128, 64, seed=6, window=window)
     q, k, v = gen_dev(w)
     run = U.run_prefill(w, q, k, v, want_idx=False)
-    cuts = [((n * s // 4 + 63) // 64) * 64 for s in (1, 2, 3)]
-    rows = [(0, r, i) for r in (0, 1) for c in cuts for i in (c - 64, c - 1, c, c + 1, c + 63)]
-    rows += [(0, r, i) for r in (0, 1) for i in (0, 63, 64, 127, 128, n - 1)]
+    cuts = [c for c in ((cap + 1 + window) * 64 for cap in (512, 1024, 1536)) if c + 64 <= n]
+    toks = [i for c in cuts for i in (c - 64, c - 1, c, c + 1, c + 63)]
+    toks += [0, 63, 64, 127, 128, 20000, 51234, n - 1] + ([83211] if n > 83211 else [])
+    rows = [(0, r, i) for r in range(h_kv) for i in toks if i < n]
     rep, err = U.check_against_oracle(w, q, k, v, run, rows)
-    print(f"token ranges: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
+    print(f"token ranges {name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
 def test_rising_logits_exercise_the_rescale_path():
