@@ -539,6 +539,14 @@ def main():
         orc_res.update(oracle_on_host(others, min(3.0, a.cpu_seconds)))
     assert torch.cuda.is_available(), "bench.py needs the GPU"
 
+    if a.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     if a.only:
         g_ = float(a.only.split("gamma")[1])
         if a.only.startswith("c2"):
@@ -565,14 +573,6 @@ def main():
                           "data": "synthetic", "config": {"workload": wb.name}, "ms_forward": r["ms_forward"],
                           "chunk_sparsity": r["sparsity"], "f_alg_forward": r["f_alg"]}))
         return
-    if a.calib_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-        torch.cuda.empty_cache()
     sens = Sensors()
     main_res = bench_prefill(w, a.steps, a.warmup, torch, B, make_inputs, sensors=sens)
     sens_main = main_res["sensors"]
