@@ -179,10 +179,10 @@ int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache,
 /* dash_attn_decode for callers that cannot allocate device memory or carry a workspace
  * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
  * the same step with the same kernels and the same results, except that the scratch
- * (attended-chunk lists when not asked for, fp32 routing scores, split-KV partial results)
+ * (attended-chunk lists when not asked for, split-KV partial results)
  * lives in an 8 MiB array inside the library, one per GPU, held until the process ends.
  * The call allocates nothing.  DASH_EWORKSPACE if dash_attn_workspace_bytes(p) exceeds
- * 8 MiB (the 128k-token decode step of 16 sequences x 8 kv-heads needs 6.3 MiB).
+ * 8 MiB (the 128k-token decode step of 16 sequences x 8 kv-heads needs 2.1 MiB).
  * Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different
  * streams or threads) race; nothing in it has to survive from one call to the next. */
 int dash_attn_decode_static(const dash_params* p, const void* q, const void* k_cache,

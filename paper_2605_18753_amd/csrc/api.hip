@@ -90,7 +90,9 @@ int make_layout(const dash_params* p, Layout* L, bool routing) {
   L->off_mask = off;  off += align256(rows * L->words * 4);
   L->off_bias = off;  off += align256(rows * L->t_all * 4);
   L->off_scores = off;
-  if (!L->use_mfma) off += align256((size_t)p->batch * p->h_q * p->n_q * (L->t_c > 0 ? L->t_c : 1) * 4);
+  // fp32 score rows: fp32 prefill only (a decode step keeps its scores in LDS)
+  if (!L->use_mfma && !(p->n_q == 1 && p->causal))
+    off += align256((size_t)p->batch * p->h_q * p->n_q * (L->t_c > 0 ? L->t_c : 1) * 4);
   L->off_part = off;
   if (decode_mfma) off += align256((size_t)p->batch * p->h_kv * splits * g * (p->head_dim + 2) * 4);
   L->total = off > 0 ? off : 256;
@@ -122,6 +124,8 @@ static int run_stage1(const dash_params* p, const Layout& L, const void* q, cons
   hipError_t e;
   if (L.use_mfma) {
     e = launch_s1_route(*p, L, q, kbar, reinterpret_cast<uint16_t*>(ws + L.off_ksplit), nullptr, out, st);
+  } else if (p->n_q == 1 && p->causal) {
+    e = launch_s1_decode(*p, L, q, kbar, out, st);   // scores, threshold and lists in one launch
   } else {
     float* scores = reinterpret_cast<float*>(ws + L.off_scores);
     e = launch_s1_scores_f32(*p, L, q, kbar, scores, st);

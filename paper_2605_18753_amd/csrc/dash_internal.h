@@ -69,6 +69,8 @@ hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const voi
 // otherwise the scores are read from `scores` (written by launch_s1_scores_f32).
 hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q, const float* kbar,
                            uint16_t* ksplit, const float* scores, const S1Out& out, hipStream_t st);
+hipError_t launch_s1_decode(const dash_params& p, const Layout& L, const void* q, const float* kbar,
+                            const S1Out& out, hipStream_t st);
 hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, const void* k,
                           const void* v, void* o, const uint32_t* mask, const float* bias,
                           bool dense, hipStream_t st);

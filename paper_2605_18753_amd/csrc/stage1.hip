@@ -342,19 +342,19 @@ __device__ __forceinline__ void emit_token(const float* S, const S1Args& a, uint
 // the slots below it, exchanged through LDS, as are the partial sums of ln w.  Same
 // arithmetic per chunk as emit_token; the sums are combined wave by wave, so mu may
 // differ from the single-wave order in the last place.
-template <int NJ>
+template <int NJ, int NWV = 4>
 __device__ __forceinline__ void emit_token_wg(const float* S, const S1Args& a, uint32_t* mw, int* xcnt,
                                               float* xsum, int tok, int n_cand, int lane, int wave,
                                               int b, int r) {
-  constexpr int NW = NJ / 4;              // slots per wave
+  constexpr int NW = (NJ + NWV - 1) / NWV;   // slots per wave (NWV waves in the workgroup)
   const float inv_g = 1.f / (float)a.g_q;
   float lw[NW];
   float slog = 0.f, nsup = 0.f;
 #pragma unroll
   for (int jj = 0; jj < NW; jj++) {
-    const int c = lane + 64 * (wave + 4 * jj);
+    const int c = lane + 64 * (wave + NWV * jj);
     float s = 0.f;
-    if (c < n_cand)
+    if (wave + NWV * jj < NJ && c < n_cand)
       for (int h = 0; h < a.g_q; h++) s += S[h * a.ld + c];
     s *= inv_g;
     lw[jj] = s > 0.f ? __builtin_amdgcn_logf(s) * 0.6931471805599453f : INFINITY;   // +inf marks "not routed"
@@ -366,13 +366,23 @@ __device__ __forceinline__ void emit_token_wg(const float* S, const S1Args& a, u
 #pragma unroll
   for (int jj = 0; jj < NW; jj++) {
     bal[jj] = __ballot(lw[jj] != INFINITY);
-    if (lane == 0) xcnt[wave + 4 * jj] = __popcll(bal[jj]);
+    if (lane == 0 && wave + NWV * jj < NJ) xcnt[wave + NWV * jj] = __popcll(bal[jj]);
   }
-  if (lane == 0) { xsum[wave] = slog; xsum[4 + wave] = nsup; }
-  for (int wi = threadIdx.x; wi < a.words; wi += 256) mw[wi] = 0u;
+  if (lane == 0) { xsum[wave] = slog; xsum[NWV + wave] = nsup; }
+  for (int wi = threadIdx.x; wi < a.words; wi += 64 * NWV) mw[wi] = 0u;
   __syncthreads();
-  const float slog_t = (xsum[0] + xsum[1]) + (xsum[2] + xsum[3]);
-  const float nsup_t = (xsum[4] + xsum[5]) + (xsum[6] + xsum[7]);
+  float slog_t, nsup_t;
+  if constexpr (NWV == 4) {
+    slog_t = (xsum[0] + xsum[1]) + (xsum[2] + xsum[3]);
+    nsup_t = (xsum[4] + xsum[5]) + (xsum[6] + xsum[7]);
+  } else {
+    slog_t = 0.f; nsup_t = 0.f;
+#pragma unroll
+    for (int w = 0; w < NWV; w += 4) {
+      slog_t += (xsum[w] + xsum[w + 1]) + (xsum[w + 2] + xsum[w + 3]);
+      nsup_t += (xsum[NWV + w] + xsum[NWV + w + 1]) + (xsum[NWV + w + 2] + xsum[NWV + w + 3]);
+    }
+  }
   const float mu = nsup_t > 0.f ? slog_t / nsup_t : 0.f;
   // members below each of this wave's slots: lane l holds the count of slot l
   const int mine = lane < NJ ? xcnt[lane] : 0;
@@ -388,7 +398,8 @@ __device__ __forceinline__ void emit_token_wg(const float* S, const S1Args& a, u
   float* obias = a.bias + base * a.t_all;
 #pragma unroll
   for (int jj = 0; jj < NW; jj++) {
-    const int j = wave + 4 * jj;
+    const int j = wave + NWV * jj;
+    if (j >= NJ) break;
     const int start = __shfl(incl - mine, j);
     const int c = lane + 64 * j;
     if (lane == 0 && 2 * j < a.words) {
@@ -420,7 +431,7 @@ __device__ __forceinline__ void emit_token_wg(const float* S, const S1Args& a, u
   __syncthreads();
   if (a.cnt && threadIdx.x == 0) a.cnt[base] = running;
   uint32_t* om = a.mask + base * a.words;
-  for (int wi = threadIdx.x; wi < a.words; wi += 256) om[wi] = mw[wi];
+  for (int wi = threadIdx.x; wi < a.words; wi += 64 * NWV) om[wi] = mw[wi];
 }
 
 template <int MT, int D, bool FROM_MFMA>
@@ -614,6 +625,130 @@ __global__ __launch_bounds__(256) void s1_route_kernel(S1Args a) {
   }
 }
 
+// Stage 1 of a decode step in one launch: one workgroup of 16 waves per (sequence,
+// kv-head) computes the scores of the pair's g_q query rows against all candidate
+// summaries (the arithmetic of s1_scores_f32_kernel: a 16-lane DPP row per chunk, fp32
+// FMA in the same order, row reduction), keeps them in LDS, and goes on to the threshold
+// and the lists with the same solvers and the same emission as s1_route_kernel: no score
+// row goes through HBM and the step has one dependent launch less.  The summaries are
+// streamed with eight 16-byte loads in flight per lane and the next batch of 256 chunks
+// requested before the current one is used.
+template <typename T, int D>
+__global__ __launch_bounds__(1024) void s1_decode_kernel(S1Args a) {
+  extern __shared__ float S[];   // [16][ld] score rows (g_q of them used), then the query rows [g_q][D] in fp32
+  __shared__ uint32_t mwords[64];
+  __shared__ int xcnt[32];
+  __shared__ float xsum[32];
+  constexpr int CPG = 4;         // chunks per 16-lane group and batch
+  constexpr int NV = D / 64;     // 16-byte loads per chunk and lane
+  const int r = blockIdx.x % a.h_kv, b = blockIdx.x / a.h_kv;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (a.seq_lens) a.pos0 = min(max(a.seq_lens[b], 1), a.n_kv) - 1;   // per-sequence cache length
+  int n_cand = max(a.pos0 / a.block - a.window, 0);
+  if (n_cand > a.t_c) n_cand = a.t_c;
+  float* qs = S + 16 * a.ld;
+
+  if (n_cand > 0) {
+    const T* qg = (const T*)a.q + b * a.qs_b + (int64_t)r * a.g_q * a.qs_h;
+    for (int i = threadIdx.x; i < a.g_q * D; i += 1024) qs[i] = elem<T>::ld(qg + (i / D) * a.qs_h + (i % D));
+    // the 16-lane-row solver (rows of up to 512 chunks) reads four rows at a time: zero the unused ones
+    if (n_cand <= 512)
+      for (int i = threadIdx.x; i < (16 - a.g_q) * n_cand; i += 1024) S[(a.g_q + i / n_cand) * a.ld + i % n_cand] = 0.f;
+    __syncthreads();
+    const int cl = threadIdx.x >> 4, l16 = threadIdx.x & 15;
+    const float* kbase = a.kbar + ((int64_t)b * a.h_kv + r) * a.t_c * D + 4 * l16;
+    f32x4 kk[2][CPG][NV];
+    auto load_batch = [&](int c0, f32x4 (&dst)[CPG][NV]) {
+#pragma unroll
+      for (int u = 0; u < CPG; u++) {
+        const int c = c0 + u * 64 + cl;
+        const float* kp = kbase + (int64_t)(c < n_cand ? c : n_cand - 1) * D;
+#pragma unroll
+        for (int i = 0; i < NV; i++) dst[u][i] = *reinterpret_cast<const f32x4*>(kp + 64 * i);
+      }
+    };
+    auto use_batch = [&](int c0, const f32x4 (&src)[CPG][NV]) {
+      for (int h = 0; h < a.g_q; h++) {
+        f32x4 qv[NV];
+#pragma unroll
+        for (int i = 0; i < NV; i++) qv[i] = *reinterpret_cast<const f32x4*>(qs + h * D + 4 * l16 + 64 * i);
+#pragma unroll
+        for (int u = 0; u < CPG; u++) {
+          float acc = 0.f;
+#pragma unroll
+          for (int i = 0; i < NV; i++)
+#pragma unroll
+            for (int e = 0; e < 4; e++) acc = fmaf(qv[i][e], src[u][i][e], acc);
+          acc = row16_sum(acc);
+          const int c = c0 + u * 64 + cl;
+          if (l16 == 0 && c < n_cand) S[h * a.ld + c] = acc * a.xscale;
+        }
+      }
+    };
+    constexpr int STEP = 64 * CPG;
+    load_batch(0, kk[0]);
+    for (int c0 = 0; c0 < n_cand; c0 += 2 * STEP) {
+      if (c0 + STEP < n_cand) load_batch(c0 + STEP, kk[1]);
+      use_batch(c0, kk[0]);
+      if (c0 + STEP < n_cand) {
+        if (c0 + 2 * STEP < n_cand) load_batch(c0 + 2 * STEP, kk[0]);
+        use_batch(c0 + STEP, kk[1]);
+      }
+    }
+  }
+  __syncthreads();
+
+  const int nj = (n_cand + 63) >> 6;
+  if (n_cand > 0) {
+    int mode;
+    if (a.pexp < 1.f) mode = MODE_BISECT;
+    else if (a.pexp == 1.f) mode = MODE_P1;
+    else if (a.pexp == 2.f) mode = MODE_P2;
+    else if (a.pexp == 4.f) mode = MODE_P4;
+    else mode = MODE_GEN;
+    if (n_cand <= 512) {
+      // four rows per wave, one per DPP row: waves 0..3 cover the 16 rows
+      if (wave < 4) {
+#define DASH_SOLVE16(NJ_)                                                                           \
+  switch (mode) {                                                                                   \
+    case MODE_P1: solve_wave_rows16<NJ_, MODE_P1>(S, a, wave, 1, n_cand, lane, b, r, 0); break;     \
+    case MODE_P2: solve_wave_rows16<NJ_, MODE_P2>(S, a, wave, 1, n_cand, lane, b, r, 0); break;     \
+    case MODE_P4: solve_wave_rows16<NJ_, MODE_P4>(S, a, wave, 1, n_cand, lane, b, r, 0); break;     \
+    case MODE_GEN: solve_wave_rows16<NJ_, MODE_GEN>(S, a, wave, 1, n_cand, lane, b, r, 0); break;   \
+    default: solve_wave_rows16<NJ_, MODE_BISECT>(S, a, wave, 1, n_cand, lane, b, r, 0); break;      \
+  }
+        if (n_cand <= 64) { DASH_SOLVE16(4) }
+        else if (n_cand <= 128) { DASH_SOLVE16(8) }
+        else if (n_cand <= 256) { DASH_SOLVE16(16) }
+        else { DASH_SOLVE16(32) }
+#undef DASH_SOLVE16
+      }
+    } else if (wave < a.g_q) {
+      // one row per wave, all rows at once
+      float t;
+#define DASH_SOLVE(NJ_)                                                                             \
+  switch (mode) {                                                                                   \
+    case MODE_P1: solve_rows<NJ_, 1, MODE_P1>(S, a.ld, wave, n_cand, a.alpha, a.pexp, lane, &t); break;   \
+    case MODE_P2: solve_rows<NJ_, 1, MODE_P2>(S, a.ld, wave, n_cand, a.alpha, a.pexp, lane, &t); break;   \
+    case MODE_P4: solve_rows<NJ_, 1, MODE_P4>(S, a.ld, wave, n_cand, a.alpha, a.pexp, lane, &t); break;   \
+    case MODE_GEN: solve_rows<NJ_, 1, MODE_GEN>(S, a.ld, wave, n_cand, a.alpha, a.pexp, lane, &t); break; \
+    default: solve_rows<NJ_, 1, MODE_BISECT>(S, a.ld, wave, n_cand, a.alpha, a.pexp, lane, &t); break;    \
+  }
+      if (nj <= 16) { DASH_SOLVE(16) } else { DASH_SOLVE(32) }
+#undef DASH_SOLVE
+      if (a.tau && lane == 0) a.tau[((int64_t)b * a.h_q + r * a.g_q + wave) * a.n_q] = t;
+    }
+  } else if (a.tau) {
+    if (threadIdx.x < a.g_q) a.tau[((int64_t)b * a.h_q + r * a.g_q + threadIdx.x) * a.n_q] = 0.f;
+  }
+  __syncthreads();
+
+  if (nj <= 4) emit_token_wg<4, 16>(S, a, mwords, xcnt, xsum, 0, n_cand, lane, wave, b, r);
+  else if (nj <= 8) emit_token_wg<8, 16>(S, a, mwords, xcnt, xsum, 0, n_cand, lane, wave, b, r);
+  else if (nj <= 16) emit_token_wg<16, 16>(S, a, mwords, xcnt, xsum, 0, n_cand, lane, wave, b, r);
+  else emit_token_wg<32, 16>(S, a, mwords, xcnt, xsum, 0, n_cand, lane, wave, b, r);
+}
+
 // fp32 scores for fp32 inputs and for decode: one 16-lane DPP row per chunk,
 // coalesced float4 reads of the fp32 summaries, fp32 FMA, row reduction.  A
 // workgroup covers 64 chunks (four per DPP row) and issues all its summary loads
@@ -712,6 +847,52 @@ __global__ __launch_bounds__(256) void ksplit_kernel(const float* __restrict__ k
   o[2 * d] = (uint16_t)(__float_as_uint(r2) >> 16);
 }
 
+static S1Args make_s1_args(const dash_params& p, const Layout& L, const void* q, const float* kbar, const S1Out& out) {
+  S1Args a;
+  a.q = q; a.ksplit = nullptr; a.scores = nullptr; a.kbar = kbar;
+  a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
+  a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv;
+  a.block = p.block_size; a.seq_lens = L.seq_lens;
+  a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal; a.window = p.window;
+  a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
+  a.xscale = L.xscale; a.pexp = L.pexp; a.alpha = p.alpha; a.inv_sigma = 1.f / p.sigma;
+  a.ld = 0; a.tok_base = 0; a.tok_end = p.n_q;
+  return a;
+}
+
+// Stage 1 of a decode step (n_q = 1, causal): one launch, one workgroup per (sequence, kv-head).
+hipError_t launch_s1_decode(const dash_params& p, const Layout& L, const void* q, const float* kbar,
+                            const S1Out& out, hipStream_t st) {
+  S1Args a = make_s1_args(p, L, q, kbar, out);
+  int max_cand = L.t_c;
+  if (!L.seq_lens) {
+    max_cand = L.pos0 / p.block_size - p.window;
+    if (max_cand > L.t_c) max_cand = L.t_c;
+    if (max_cand < 0) max_cand = 0;
+  }
+  a.ld = ((max_cand + 15) / 16) * 16 + 4;
+  const size_t lds = ((size_t)16 * a.ld + (size_t)L.g_q * p.head_dim) * 4;
+  const dim3 grid((unsigned)(p.batch * p.h_kv), 1, 1);
+  static LdsOptIn opt_in[4];   // one per kernel below
+  const void* kern;
+  int which;
+  if (p.dtype == DASH_BF16) {
+    which = p.head_dim == 128 ? 0 : 1;
+    kern = p.head_dim == 128 ? (const void*)s1_decode_kernel<uint16_t, 128> : (const void*)s1_decode_kernel<uint16_t, 64>;
+  } else {
+    which = p.head_dim == 128 ? 2 : 3;
+    kern = p.head_dim == 128 ? (const void*)s1_decode_kernel<float, 128> : (const void*)s1_decode_kernel<float, 64>;
+  }
+  if (hipError_t e = allow_dyn_lds(kern, lds, opt_in[which]); e != hipSuccess) return e;
+  switch (which) {
+    case 0: hipLaunchKernelGGL((s1_decode_kernel<uint16_t, 128>), grid, dim3(1024), lds, st, a); break;
+    case 1: hipLaunchKernelGGL((s1_decode_kernel<uint16_t, 64>), grid, dim3(1024), lds, st, a); break;
+    case 2: hipLaunchKernelGGL((s1_decode_kernel<float, 128>), grid, dim3(1024), lds, st, a); break;
+    default: hipLaunchKernelGGL((s1_decode_kernel<float, 64>), grid, dim3(1024), lds, st, a); break;
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q, const float* kbar,
                            uint16_t* ksplit, const float* scores, const S1Out& out, hipStream_t st) {
   if (ksplit != nullptr && L.t_c > 0) {
@@ -722,14 +903,8 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  S1Args a;
-  a.q = q; a.ksplit = ksplit; a.scores = scores;
-  a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
-  a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv;
-  a.block = p.block_size; a.seq_lens = L.seq_lens;
-  a.t_c = L.t_c; a.t_all = L.t_all; a.words = L.words; a.pos0 = L.pos0; a.causal = p.causal; a.window = p.window;
-  a.qs_b = p.q_stride[0]; a.qs_h = p.q_stride[1]; a.qs_t = p.q_stride[2];
-  a.xscale = L.xscale; a.pexp = L.pexp; a.alpha = p.alpha; a.inv_sigma = 1.f / p.sigma;
+  S1Args a = make_s1_args(p, L, q, kbar, out);
+  a.ksplit = ksplit; a.scores = scores;
   const bool mfma = L.use_mfma && ksplit != nullptr;
   // Token ranges, each launched with the kernel and the sizes that fit its longest row
   // (causal rows grow with the position; boundaries at multiples of 64 tokens, longest

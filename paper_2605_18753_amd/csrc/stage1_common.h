@@ -9,6 +9,7 @@ struct S1Args {
   const void* q;
   const uint16_t* ksplit;
   const float* scores;
+  const float* kbar;         // fp32 summaries (the decode kernel scores against them itself)
   uint32_t* mask;
   int32_t* cnt;
   int32_t* idx;

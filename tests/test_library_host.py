@@ -50,7 +50,8 @@ def test_workspace_and_list_sizes():
     assert B.list_stride(p2) == 16
     pd = params(n_q=1, n_kv=131072, batch=16, h_q=32, h_kv=8)
     assert B.list_stride(pd) == 2048 and B.mask_words(pd) == 64
-    assert B.workspace_bytes(pd) > 16 * 32 * 2047 * 4
+    # a decode step keeps its scores on chip: the bias lists and the split-KV partials are what it needs
+    assert 16 * 8 * 2048 * 4 < B.workspace_bytes(pd) < 16 * 32 * 2047 * 4
 
 
 @pytest.mark.parametrize("kw,code", [

@@ -53,10 +53,10 @@ def test_decode_on_the_built_in_scratch_equals_decode_on_a_workspace(with_lists)
 
 
 def test_static_decode_rejects_what_does_not_fit():
-    # 64 sequences x 8 kv-heads at 128k tokens: the scores and lists alone exceed 8 MiB
+    # 512 sequences x 8 kv-heads at 128k tokens: the bias lists alone exceed 8 MiB
     lib = B.load_library()
     p = B.dash_params()
-    for k_, v_ in dict(batch=64, h_q=32, h_kv=8, n_q=1, n_kv=131072, head_dim=128, block_size=64, causal=1,
+    for k_, v_ in dict(batch=512, h_q=32, h_kv=8, n_q=1, n_kv=131072, head_dim=128, block_size=64, causal=1,
                        dtype=B.DASH_BF16, alpha=1.5, gamma=1.0, sigma=1.0, scale=0.0).items():
         setattr(p, k_, v_)
     for name, heads, n in (("q_stride", 32, 1), ("k_stride", 8, 131072), ("v_stride", 8, 131072), ("o_stride", 32, 1)):
