@@ -93,7 +93,10 @@ int32_t dash_list_stride(const dash_params* p);
 int32_t dash_mask_words(const dash_params* p);
 
 /* Bytes of device scratch the calls below need for these parameters (host
- * computation only).  The workspace must be 256-byte aligned. */
+ * computation only).  The workspace must be 256-byte aligned.  One query serves every
+ * call, dense_attn included, so it accepts what any of them accepts: a non-causal n_kv
+ * that is not a multiple of block_size gets a size here and DASH_EINVAL from the
+ * routing calls (a tail chunk has no summary), which dense_attn does not need. */
 int dash_attn_workspace_bytes(const dash_params* p, size_t* out_bytes);
 
 /* Stage 0 (Eq. 3 at zero summary query = uniform mean; Alg. 1).
