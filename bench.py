@@ -234,7 +234,7 @@ def bench_decode(w, steps, warmup, torch, B, make_inputs):
     return res
 
 
-def paper_protocol(steps, warmup, torch, B):
+def paper_protocol(steps, warmup, torch, B, lengths=(16384, 32768, 65536, 98304)):
     """Stage-2 speed-up over the in-library dense attention on the shapes and the
     randomised masks of the paper's kernel benchmark (Sec. 5.2, App. B.2, Table 5).
     Stage 0/1 do not depend on the mask; their time on the same tensors is given
@@ -247,7 +247,7 @@ def paper_protocol(steps, warmup, torch, B):
     gen.manual_seed(0)
     out = {"shape": {"h_q": h_q, "h_kv": h_kv, "head_dim": d, "block": blk, "dtype": "bf16"},
            "prefill_batch": 1, "decode_batch": 24, "prefill": {}, "decode": {}}
-    for n in (16384, 32768, 65536, 98304):
+    for n in lengths:
         # ---- prefill, batch 1
         q = torch.randn((1, h_q, n, d), generator=gen, device=dev).bfloat16()
         k = torch.randn((1, h_kv, n, d), generator=gen, device=dev).bfloat16()
@@ -582,6 +582,8 @@ def main():
     sweep = None if a.no_sweep else c4_sweep(torch, B, make_inputs, C4, a.small)
     c1 = c1_time(torch, B, make_inputs, C1, a.steps)
     mb = None if a.small else microbench(torch, a.steps)
+    # the paper's own benchmark shape (GQA group 16, randomised masks) at its 32K point; all four lengths: --paper-protocol
+    pp32 = None if (a.small or a.no_sweep) else paper_protocol(a.steps, a.warmup, torch, B, lengths=(32768,))
     dec = None
     if not a.no_decode:
         dec = dict(gamma1=bench_decode(wd, max(a.steps, 20), a.warmup, torch, B, make_inputs),
@@ -633,6 +635,7 @@ def main():
             "sensors": sens_main,
             "C1_fp32_single_head": c1,
             "C4_sweep_128k": sweep,
+            "paper_protocol_32k": pp32,
             # the oracle on the host cores for the other configurations: rows per second on a 3 s sample and
             # the whole configuration's time extrapolated from it (rows are independent)
             "oracle_on_host": None if orc_res is None else {
