@@ -116,7 +116,7 @@ static int check_ws(const Layout& L, void* ws, size_t bytes) {
 
 static int run_stage1(const dash_params* p, const Layout& L, const void* q, const float* kbar,
                       uint32_t* mask, int32_t* cnt, int32_t* idx, float* bias, float* tau,
-                      char* ws, hipStream_t st) {
+                      char* ws, hipStream_t st, const void* k_upd = nullptr, float* kbar_upd = nullptr) {
   S1Out out;
   out.mask = mask ? mask : reinterpret_cast<uint32_t*>(ws + L.off_mask);
   out.bias = bias ? bias : reinterpret_cast<float*>(ws + L.off_bias);
@@ -125,7 +125,7 @@ static int run_stage1(const dash_params* p, const Layout& L, const void* q, cons
   if (L.use_mfma) {
     e = launch_s1_route(*p, L, q, kbar, reinterpret_cast<uint16_t*>(ws + L.off_ksplit), nullptr, out, st);
   } else if (p->n_q == 1 && p->causal) {
-    e = launch_s1_decode(*p, L, q, kbar, out, st);   // scores, threshold and lists in one launch
+    e = launch_s1_decode(*p, L, q, kbar, out, k_upd, kbar_upd, st);   // scores, threshold and lists in one launch
   } else {
     float* scores = reinterpret_cast<float*>(ws + L.off_scores);
     e = launch_s1_scores_f32(*p, L, q, kbar, scores, st);
@@ -254,15 +254,10 @@ static int decode_impl(const dash_params* p, const void* q, const void* k_cache,
   if ((rc = check_ws(L, workspace, workspace_bytes)) != DASH_OK) return rc;
   L.seq_lens = seq_lens;
   hipStream_t st = (hipStream_t)stream;
-  if (update_cache) {
-    // a current token that completes a chunk: summarise that chunk now; it becomes a
-    // candidate only for later positions
-    hipError_t e = hipSuccess;
-    if (seq_lens) e = launch_kbar_compress_completed(*p, L, k_cache, kbar_cache, st);
-    else if (p->n_kv % p->block_size == 0) e = launch_kbar_compress(*p, L, k_cache, kbar_cache, L.t_c - 1, 1, st);
-    if (e != hipSuccess) return DASH_ELAUNCH;
-  }
-  rc = run_stage1(p, L, q, kbar_cache, mask, blk_cnt, blk_idx, blk_bias, tau, (char*)workspace, st);
+  // a current token that completes a chunk: that chunk is summarised now, by extra workgroups
+  // of the Stage-1 launch; it becomes a candidate only for later positions
+  rc = run_stage1(p, L, q, kbar_cache, mask, blk_cnt, blk_idx, blk_bias, tau, (char*)workspace, st,
+                  update_cache ? k_cache : nullptr, update_cache ? kbar_cache : nullptr);
   if (rc != DASH_OK) return rc;
   return run_stage2(p, L, q, k_cache, v_cache, o, mask, blk_bias, (char*)workspace, false, st);
 }

@@ -8,6 +8,7 @@
 // for 64..128 bf16/fp32 inputs of comparable magnitude, so the fp32 result is
 // the correctly rounded mean independent of summation order.
 #include "common.h"
+#include "compress_body.h"
 #include "dash_internal.h"
 
 namespace dash {
@@ -15,50 +16,11 @@ namespace dash {
 template <typename T>
 __global__ __launch_bounds__(256) void kbar_compress_kernel(
     const T* __restrict__ k, float* __restrict__ kbar, int block,
-    int d, int t_c, int first_chunk, int64_t ks_b, int64_t ks_h, int64_t ks_t,
-    const int32_t* __restrict__ seq_lens, int n_kv) {
-  constexpr int VEC = elem<T>::kVec;
+    int d, int t_c, int first_chunk, int64_t ks_b, int64_t ks_h, int64_t ks_t) {
   __shared__ double sm[2048];
-  int c = first_chunk + blockIdx.x;
+  const int c = first_chunk + blockIdx.x;
   const int r = blockIdx.y, b = blockIdx.z, h_kv = gridDim.y;
-  if (seq_lens) {
-    // decode with per-sequence lengths: only the chunk that the sequence's current
-    // token completes, if it completes one
-    const int len = min(max(seq_lens[b], 1), n_kv);
-    if (len % block != 0) return;
-    c = len / block - 1;
-  }
-  const int cg_n = d / VEC;              // 16-byte column groups per row
-  const int rp = 256 / cg_n;             // rows covered per pass
-  const int cg = threadIdx.x % cg_n, r0 = threadIdx.x / cg_n;
-  const T* base = k + b * ks_b + r * ks_h + (int64_t)c * block * ks_t + cg * VEC;
-  double acc[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; e++) acc[e] = 0.0;
-  for (int row = r0; row < block; row += rp) {
-    const u32x4 raw = *reinterpret_cast<const u32x4*>(base + (int64_t)row * ks_t);
-    if constexpr (VEC == 8) {
-#pragma unroll
-      for (int e = 0; e < 4; e++) {
-        acc[2 * e] += (double)bf16_lo(raw[e]);
-        acc[2 * e + 1] += (double)bf16_hi(raw[e]);
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; e++) acc[e] += (double)__uint_as_float(raw[e]);
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < VEC; e++) sm[r0 * d + cg * VEC + e] = acc[e];
-  __syncthreads();
-  const int col = threadIdx.x;
-  if (col < d) {
-    double s = 0.0;
-    for (int rr = 0; rr < rp; rr++) s += sm[rr * d + col];
-    const float mean = (float)(s * (1.0 / (double)block));
-    const int64_t o = (((int64_t)b * h_kv + r) * t_c + c) * d + col;
-    kbar[o] = mean;
-  }
+  kbar_block_mean<T>(k, kbar, sm, block, d, t_c, c, r, b, h_kv, ks_b, ks_h, ks_t);
 }
 
 
@@ -276,28 +238,11 @@ hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const voi
   if (p.dtype == DASH_BF16)
     hipLaunchKernelGGL(kbar_compress_kernel<uint16_t>, grid, blk, 0, st, (const uint16_t*)k, kbar,
                        p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0],
-                       p.k_stride[1], p.k_stride[2], (const int32_t*)nullptr, p.n_kv);
+                       p.k_stride[1], p.k_stride[2]);
   else
     hipLaunchKernelGGL(kbar_compress_kernel<float>, grid, blk, 0, st, (const float*)k, kbar,
                        p.block_size, p.head_dim, L.t_c, first_chunk, p.k_stride[0], p.k_stride[1],
-                       p.k_stride[2], (const int32_t*)nullptr, p.n_kv);
-  return hipGetLastError();
-}
-
-// Decode with per-sequence lengths (L.seq_lens): one workgroup per (kv-head, batch)
-// summarises the chunk that sequence's current token completes, if any.
-hipError_t launch_kbar_compress_completed(const dash_params& p, const Layout& L, const void* k, float* kbar,
-                                          hipStream_t st) {
-  if (L.t_c == 0) return hipSuccess;
-  dim3 grid(1, p.h_kv, p.batch), blk(256);
-  if (p.dtype == DASH_BF16)
-    hipLaunchKernelGGL(kbar_compress_kernel<uint16_t>, grid, blk, 0, st, (const uint16_t*)k, kbar,
-                       p.block_size, p.head_dim, L.t_c, 0, p.k_stride[0], p.k_stride[1], p.k_stride[2],
-                       L.seq_lens, p.n_kv);
-  else
-    hipLaunchKernelGGL(kbar_compress_kernel<float>, grid, blk, 0, st, (const float*)k, kbar,
-                       p.block_size, p.head_dim, L.t_c, 0, p.k_stride[0], p.k_stride[1], p.k_stride[2],
-                       L.seq_lens, p.n_kv);
+                       p.k_stride[2]);
   return hipGetLastError();
 }
 

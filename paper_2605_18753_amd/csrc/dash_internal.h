@@ -58,8 +58,6 @@ struct S1Out {
 
 hipError_t launch_kbar_compress(const dash_params& p, const Layout& L, const void* k, float* kbar,
                                 int first_chunk, int n_chunks, hipStream_t st);
-hipError_t launch_kbar_compress_completed(const dash_params& p, const Layout& L, const void* k, float* kbar,
-                                          hipStream_t st);
 hipError_t launch_kbar_summarize(const dash_params& p, const Layout& L, const void* k, const float* qbar,
                                  const int64_t* qs, float* kbar, int first_chunk, int n_chunks,
                                  hipStream_t st);
@@ -70,7 +68,7 @@ hipError_t launch_s1_scores_f32(const dash_params& p, const Layout& L, const voi
 hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q, const float* kbar,
                            uint16_t* ksplit, const float* scores, const S1Out& out, hipStream_t st);
 hipError_t launch_s1_decode(const dash_params& p, const Layout& L, const void* q, const float* kbar,
-                            const S1Out& out, hipStream_t st);
+                            const S1Out& out, const void* k_upd, float* kbar_upd, hipStream_t st);
 hipError_t launch_s2_mfma(const dash_params& p, const Layout& L, const void* q, const void* k,
                           const void* v, void* o, const uint32_t* mask, const float* bias,
                           bool dense, hipStream_t st);

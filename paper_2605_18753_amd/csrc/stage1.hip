@@ -24,6 +24,7 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "compress_body.h"
 #include "dash_internal.h"
 #include "stage1_common.h"
 
@@ -641,8 +642,19 @@ __global__ __launch_bounds__(1024) void s1_decode_kernel(S1Args a) {
   __shared__ float xsum[32];
   constexpr int CPG = 4;         // chunks per 16-lane group and batch
   constexpr int NV = D / 64;     // 16-byte loads per chunk and lane
-  const int r = blockIdx.x % a.h_kv, b = blockIdx.x / a.h_kv;
+  const int pairs = a.h_kv * a.batch;
+  const int r = blockIdx.x % a.h_kv, b = (blockIdx.x % pairs) / a.h_kv;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if ((int)blockIdx.x >= pairs) {
+    // The second half of the grid (launched only with a.k_upd): a current token that completes
+    // a chunk has that chunk summarised now.  The chunk is the query's own, not a candidate of
+    // this step, so nothing in the other workgroups reads what is written here.
+    const int len = a.seq_lens ? min(max(a.seq_lens[b], 1), a.n_kv) : a.n_kv;
+    if (len % a.block != 0) return;
+    kbar_block_mean<T>((const T*)a.k_upd, a.kbar_upd, reinterpret_cast<double*>(S), a.block, D, a.t_c,
+                       len / a.block - 1, r, b, a.h_kv, a.ks_b, a.ks_h, a.ks_t);
+    return;
+  }
   if (a.seq_lens) a.pos0 = min(max(a.seq_lens[b], 1), a.n_kv) - 1;   // per-sequence cache length
   int n_cand = max(a.pos0 / a.block - a.window, 0);
   if (n_cand > a.t_c) n_cand = a.t_c;
@@ -849,7 +861,7 @@ __global__ __launch_bounds__(256) void ksplit_kernel(const float* __restrict__ k
 
 static S1Args make_s1_args(const dash_params& p, const Layout& L, const void* q, const float* kbar, const S1Out& out) {
   S1Args a;
-  a.q = q; a.ksplit = nullptr; a.scores = nullptr; a.kbar = kbar;
+  a.q = q; a.ksplit = nullptr; a.scores = nullptr; a.kbar = kbar; a.k_upd = nullptr; a.kbar_upd = nullptr; a.ks_b = a.ks_h = a.ks_t = 0;
   a.mask = out.mask; a.cnt = out.cnt; a.idx = out.idx; a.bias = out.bias; a.tau = out.tau;
   a.batch = p.batch; a.h_q = p.h_q; a.h_kv = p.h_kv; a.g_q = L.g_q; a.n_q = p.n_q; a.n_kv = p.n_kv;
   a.block = p.block_size; a.seq_lens = L.seq_lens;
@@ -862,8 +874,12 @@ static S1Args make_s1_args(const dash_params& p, const Layout& L, const void* q,
 
 // Stage 1 of a decode step (n_q = 1, causal): one launch, one workgroup per (sequence, kv-head).
 hipError_t launch_s1_decode(const dash_params& p, const Layout& L, const void* q, const float* kbar,
-                            const S1Out& out, hipStream_t st) {
+                            const S1Out& out, const void* k_upd, float* kbar_upd, hipStream_t st) {
   S1Args a = make_s1_args(p, L, q, kbar, out);
+  // k_upd: also summarise the chunk the current token completes, in a second set of workgroups
+  // (uniform lengths: only if n_kv is a multiple of the chunk size; per-sequence lengths: decided per sequence)
+  const bool upd = k_upd && kbar_upd && L.t_c > 0 && (L.seq_lens || p.n_kv % p.block_size == 0);
+  if (upd) { a.k_upd = k_upd; a.kbar_upd = kbar_upd; a.ks_b = p.k_stride[0]; a.ks_h = p.k_stride[1]; a.ks_t = p.k_stride[2]; }
   int max_cand = L.t_c;
   if (!L.seq_lens) {
     max_cand = L.pos0 / p.block_size - p.window;
@@ -871,8 +887,9 @@ hipError_t launch_s1_decode(const dash_params& p, const Layout& L, const void* q
     if (max_cand < 0) max_cand = 0;
   }
   a.ld = ((max_cand + 15) / 16) * 16 + 4;
-  const size_t lds = ((size_t)16 * a.ld + (size_t)L.g_q * p.head_dim) * 4;
-  const dim3 grid((unsigned)(p.batch * p.h_kv), 1, 1);
+  size_t lds = ((size_t)16 * a.ld + (size_t)L.g_q * p.head_dim) * 4;
+  if (upd && lds < 2048 * sizeof(double)) lds = 2048 * sizeof(double);   // the block mean's partial sums
+  const dim3 grid((unsigned)(p.batch * p.h_kv * (upd ? 2 : 1)), 1, 1);
   static LdsOptIn opt_in[4];   // one per kernel below
   const void* kern;
   int which;

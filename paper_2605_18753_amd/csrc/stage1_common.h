@@ -10,6 +10,8 @@ struct S1Args {
   const uint16_t* ksplit;
   const float* scores;
   const float* kbar;         // fp32 summaries (the decode kernel scores against them itself)
+  // decode: the cache update folded into the Stage-1 launch (extra workgroups), or k_upd == null
+  const void* k_upd; float* kbar_upd; int64_t ks_b, ks_h, ks_t;
   uint32_t* mask;
   int32_t* cnt;
   int32_t* idx;
