@@ -328,23 +328,25 @@ def test_decode_ragged_equals_uniform_decode_at_full_length():
     assert torch.equal(o, ref.o) and torch.equal(lists.mask, ref.lists.mask) and torch.equal(lists.cnt, ref.lists.cnt)
 
 
-@pytest.mark.parametrize("name,h_q,h_kv,n,window", [
-    ("g2_1027_chunks", 4, 2, 65536 + 192, 1),      # rows of up to 512 chunks, then of up to 1536
-    ("g16_1538_chunks", 16, 1, 98304 + 128, 0),    # ... and a last range beyond 1536 chunks
-    ("g8_781_chunks", 8, 1, 50000, 2),
-    ("g4_2048_chunks", 4, 1, 131072, 0),           # the longest rows the lists can hold
+@pytest.mark.parametrize("name,h_q,h_kv,n,window,extra", [
+    ("g2_1027_chunks", 4, 2, 65536 + 192, 1, {}),      # rows of up to 512 chunks, then of up to 1536
+    ("g16_1538_chunks", 16, 1, 98304 + 128, 0, {}),    # ... and a last range beyond 1536 chunks
+    ("g8_781_chunks", 8, 1, 50000, 2, {}),
+    ("g4_2048_chunks", 4, 1, 131072, 0, {}),           # the longest rows the lists can hold
+    ("g2_alpha17_625_chunks", 4, 2, 40000, 0, {"alpha": 1.7}),           # general exponent on rows split over two waves
+    ("g1_alpha3_bisect_625_chunks", 2, 2, 40000, 1, {"alpha": 3.0, "offset_sigma": 0.8}),   # pure bisection on them
 ])
-def test_stage1_token_ranges_agree_with_the_oracle_at_their_boundaries(name, h_q, h_kv, n, window):
+def test_stage1_token_ranges_agree_with_the_oracle_at_their_boundaries(name, h_q, h_kv, n, window, extra):
     """A long causal bf16 prefill runs Stage 1 as several launches over token ranges, cut where
     the row length passes 512 and 1536 candidate chunks (each range has its own kernel: whole
     rows per wave, rows split over a wave pair, rows in LDS): the rows on both sides of every
     cut, rows inside every range, and the first and last rows, against the oracle."""
-    w = Workload(name, 1, h_q, h_kv, n, n, 128, 64, seed=6, window=window)
+    w = Workload(name, 1, h_q, h_kv, n, n, 128, 64, seed=6, window=window, **extra)
     q, k, v = gen_dev(w)
     run = U.run_prefill(w, q, k, v, want_idx=False)
     cuts = [c for c in ((cap + 1 + window) * 64 for cap in (512, 1024, 1536)) if c + 64 <= n]
     toks = [i for c in cuts for i in (c - 64, c - 1, c, c + 1, c + 63)]
-    toks += [0, 63, 64, 127, 128, 20000, 51234, n - 1] + [t for t in (83211, 110000, 131008) if t < n]
+    toks += [0, 63, 64, 127, 128, 20000, n - 1] + [t for t in (36000, 51234, 83211, 110000, 131008) if t < n]
     rows = [(0, r, i) for r in range(h_kv) for i in toks if i < n]
     rep, err = U.check_against_oracle(w, q, k, v, run, rows)
     print(f"token ranges {name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
