@@ -403,6 +403,29 @@ def test_chunked_prefill_continues_a_longer_cache(dtype, h_q, h_kv, n_q, n_kv, d
     assert diff <= tol, diff
 
 
+def test_chunked_prefill_against_a_long_cache_crosses_the_row_length_ranges():
+    """The last 8192 tokens of a 36864-token sequence (rows of 447 to 576 candidate chunks: the
+    token range is cut where the rows pass 512 chunks, at a position that depends on the offset of
+    the queries): sampled rows against the oracle, and masks, counts and outputs equal to the same
+    rows of one prefill over the whole sequence, whose ranges are cut elsewhere."""
+    n_q, n_kv = 8192, 36864
+    w = Workload("chunked_long", 1, 8, 2, n_q, n_kv, 128, 64, seed=29, window=1)
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    cut = (512 + 1 + 1) * 64 - (n_kv - n_q)      # first query whose row has more than 512 candidates
+    toks = [0, 1, 63, 64, cut - 64, cut - 1, cut, cut + 1, cut + 63, cut + 64, 6000, n_q - 1]
+    rep, err = U.check_against_oracle(w, q, k, v, run, [(0, r, i) for r in (0, 1) for i in toks])
+    print(f"chunked prefill, long cache: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
+    wf = w.replace(n_q=n_kv)
+    qf = torch.zeros((1, 8, n_kv, 128), dtype=q.dtype, device=DEV)
+    qf[:, :, n_kv - n_q:] = q
+    full = U.run_prefill(wf, qf, k, v, want_idx=False)
+    assert torch.equal(full.lists.mask[:, :, n_kv - n_q:], run.lists.mask)
+    assert torch.equal(full.lists.cnt[:, :, n_kv - n_q:], run.lists.cnt)
+    diff = (full.o[:, :, n_kv - n_q:].float() - run.o.float()).abs().max() / run.o.float().abs().max()
+    assert diff <= 2e-2, diff
+
+
 def _token_major(t):
     """The same values stored [batch, token, head, d] (the layout of a fused QKV projection),
     viewed as [batch, head, token, d]: head and token strides are swapped, d stays contiguous."""
