@@ -171,8 +171,9 @@ int dash_attn_prefill(const dash_params* p, const void* q, const void* k,
 /* One decode step (n_q must be 1; always causal): Stage 1 on the cached
  * summaries, then split-KV Stage 2 and the log-sum-exp merge of the partial
  * results (Sec. 3.5).  kbar_cache is in/out: if the current token completes a
- * chunk (n_kv % block_size == 0) that chunk's summary is written first; the
- * other entries are read only.  List outputs optional as above. */
+ * chunk (n_kv % block_size == 0) that chunk's summary is written by the same
+ * launch that routes (it is the query's own chunk, not a candidate of this
+ * step); the other entries are read only.  List outputs optional as above. */
 int dash_attn_decode(const dash_params* p, const void* q, const void* k_cache,
                      const void* v_cache, float* kbar_cache, void* o,
                      uint32_t* mask, int32_t* blk_cnt, int32_t* blk_idx,
@@ -203,7 +204,7 @@ int dash_attn_decode_static(const dash_params* p, const void* q, const void* k_c
  *                 clamped into that range by the kernels (never read out of bounds)
  *   update_cache  != 0: the block-mean summary of a chunk that a sequence's current
  *                 token completes (seq_lens[b] % block_size == 0) is written into
- *                 kbar_cache first, per sequence; 0: kbar_cache is read only (the
+ *                 kbar_cache, per sequence; 0: kbar_cache is read only (the
  *                 caller maintains it, e.g. with dash_kbar_summarize)
  * kbar_cache [batch,h_kv,floor(n_kv/block),d]; only the summaries of a sequence's
  * complete chunks before its current one are read.  bf16 only (DASH_EUNSUPPORTED
