@@ -193,6 +193,23 @@ def test_decode_small(n_kv, extra):
     print(f"decode {n_kv}: sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
 
 
+@pytest.mark.parametrize("name,batch,h_q,h_kv,n_kv,d,extra", [
+    ("fp32_d64", 2, 4, 2, 1500, 64, {"dtype": "fp32"}),                  # the one-launch Stage 1 on fp32 tensors
+    ("fp32_d128_chunk_completes", 1, 4, 1, 2048, 128, {"dtype": "fp32", "alpha": 2.0}),
+    ("g16_625_chunks", 2, 32, 2, 40000, 128, {}),                        # one row per wave, all sixteen waves
+    ("g16_300_chunks_window", 1, 16, 1, 19200, 128, {"window": 1}),      # four rows per wave (rows of up to 512 chunks)
+    ("g8_d64_b128", 3, 8, 1, 30000, 64, {"block": 128, "alpha": 1.25}),
+])
+def test_decode_other_types_and_groups(name, batch, h_q, h_kv, n_kv, d, extra):
+    extra = dict(extra)
+    block = extra.pop("block", 64)
+    w = Workload("decode_" + name, batch, h_q, h_kv, 1, n_kv, d, block, offset_sigma=0.7, seed=11, **extra)
+    q, k, v = gen_dev(w)
+    run = U.run_decode(w, q, k, v)
+    rep, err = U.check_against_oracle(w, q, k, v, run)
+    print(f"decode {name}: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
+
+
 def test_decode_updates_summary_cache_when_chunk_completes():
     w = Workload("decode_cache", 2, 4, 2, 1, 1024, 128, 64, offset_sigma=0.7, seed=2)
     q, k, v = gen(w)
@@ -424,6 +441,17 @@ def test_chunked_prefill_against_a_long_cache_crosses_the_row_length_ranges():
     assert torch.equal(full.lists.cnt[:, :, n_kv - n_q:], run.lists.cnt)
     diff = (full.o[:, :, n_kv - n_q:].float() - run.o.float()).abs().max() / run.o.float().abs().max()
     assert diff <= 2e-2, diff
+
+
+def test_noncausal_prefill_with_long_rows():
+    """Non-causal bf16 rows of 1024 chunks (every row has the same candidates: the whole launch goes
+    to the kernel that splits a row over two waves), 192 queries against 65536 keys."""
+    w = Workload("noncausal_long", 1, 8, 2, 192, 65536, 128, 64, causal=False, seed=31, offset_sigma=0.7)
+    q, k, v = gen_dev(w)
+    run = U.run_prefill(w, q, k, v, want_idx=False)
+    rep, err = U.check_against_oracle(w, q, k, v, run, [(0, r, i) for r in (0, 1) for i in (0, 1, 63, 64, 100, 191)])
+    print(f"non-causal long rows: rows {rep.rows} sparsity {rep.sparsity:.3f} exempt {rep.exempt} {rep.errors()}")
+    assert rep.sparsity > 0.3
 
 
 def _token_major(t):
