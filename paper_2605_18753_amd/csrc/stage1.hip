@@ -668,6 +668,82 @@ __global__ __launch_bounds__(1024) void s1_decode_kernel(S1Args a) {
       for (int i = threadIdx.x; i < (16 - a.g_q) * n_cand; i += 1024) S[(a.g_q + i / n_cand) * a.ld + i % n_cand] = 0.f;
     __syncthreads();
     const int cl = threadIdx.x >> 4, l16 = threadIdx.x & 15;
+    bool on_mfma = false;
+    if constexpr (sizeof(T) == 2) {
+      if (a.g_q >= 8) {
+        // GQA groups of 8 and 16 fill a 16-row matrix-core tile: the scores of 16 chunks at a
+        // time from v_mfma_f32_16x16x32_bf16, A = the group's query rows (exact in bf16), B =
+        // the fp32 summaries split on the fly into three bf16 pieces by truncation (exact:
+        // x = hi + mid + lo), three products per d slice into two accumulators as in the
+        // prefill kernels, so a decode step and a prefill see the same scores.  Lane
+        // (n = lane % 16, kq = lane / 16) supplies d 32 ks + 8 kq .. + 7 of chunk 16 ct + n and
+        // receives the scores of heads 4 kq .. 4 kq + 3 at that chunk.  Wave w takes the chunk
+        // tiles w, w + 16, ...; the loads of its next tile are in flight during the current one.
+        on_mfma = true;
+        constexpr int KS = D / 32;
+        const int n16 = lane & 15, kq = lane >> 4;
+        bf16x8 qf[KS];
+        {
+          const uint16_t* qp = (const uint16_t*)a.q + b * a.qs_b + (int64_t)(r * a.g_q + (n16 < a.g_q ? n16 : 0)) * a.qs_h + kq * 8;
+#pragma unroll
+          for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 32);
+        }
+        const float* kt0 = a.kbar + ((int64_t)b * a.h_kv + r) * a.t_c * D + kq * 8;
+        const int ntile_c = (n_cand + 15) >> 4;
+        f32x4 kv[2][KS][2];
+        auto load_tile = [&](int ct, f32x4 (&dst)[KS][2]) {
+          const int c = ct * 16 + n16;
+          const float* kp = kt0 + (int64_t)(c < n_cand ? c : n_cand - 1) * D;
+#pragma unroll
+          for (int ks = 0; ks < KS; ks++) {
+            dst[ks][0] = *reinterpret_cast<const f32x4*>(kp + ks * 32);
+            dst[ks][1] = *reinterpret_cast<const f32x4*>(kp + ks * 32 + 4);
+          }
+        };
+        auto use_tile = [&](int ct, const f32x4 (&src)[KS][2]) {
+          f32x4 acc_hi = {0.f, 0.f, 0.f, 0.f}, acc_lo = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ks++) {
+            u32x4 p_hi, p_mid, p_lo;
+#pragma unroll
+            for (int e2 = 0; e2 < 4; e2++) {   // elements 2 e2, 2 e2 + 1 of the lane's eight
+              uint32_t h2[2], m2[2], l2[2];
+#pragma unroll
+              for (int t = 0; t < 2; t++) {
+                const float x = src[ks][e2 >> 1][2 * (e2 & 1) + t];
+                const uint32_t hb = __float_as_uint(x) & 0xffff0000u;
+                const float r1 = x - __uint_as_float(hb);
+                const uint32_t mb = __float_as_uint(r1) & 0xffff0000u;
+                const float r2 = r1 - __uint_as_float(mb);
+                h2[t] = hb; m2[t] = mb; l2[t] = __float_as_uint(r2);
+              }
+              // the upper halves of two words side by side (element 2 e2 in the low half)
+              p_hi[e2] = __builtin_amdgcn_perm(h2[1], h2[0], 0x07060302u);
+              p_mid[e2] = __builtin_amdgcn_perm(m2[1], m2[0], 0x07060302u);
+              p_lo[e2] = __builtin_amdgcn_perm(l2[1], l2[0], 0x07060302u);
+            }
+            acc_hi = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks], __builtin_bit_cast(bf16x8, p_hi), acc_hi, 0, 0, 0);
+            acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks], __builtin_bit_cast(bf16x8, p_mid), acc_lo, 0, 0, 0);
+            acc_lo = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks], __builtin_bit_cast(bf16x8, p_lo), acc_lo, 0, 0, 0);
+          }
+          const int c = ct * 16 + n16;
+          if (c < n_cand) {
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+              if (4 * kq + j < a.g_q) S[(4 * kq + j) * a.ld + c] = (acc_hi[j] + acc_lo[j]) * a.xscale;
+          }
+        };
+        if (wave < ntile_c) load_tile(wave, kv[0]);
+        for (int ct = wave; ct < ntile_c; ct += 32) {
+          if (ct + 16 < ntile_c) load_tile(ct + 16, kv[1]);
+          use_tile(ct, kv[0]);
+          if (ct + 16 < ntile_c) {
+            if (ct + 32 < ntile_c) load_tile(ct + 32, kv[0]);
+            use_tile(ct + 16, kv[1]);
+          }
+        }
+      }
+    }
     const float* kbase = a.kbar + ((int64_t)b * a.h_kv + r) * a.t_c * D + 4 * l16;
     f32x4 kk[2][CPG][NV];
     auto load_batch = [&](int c0, f32x4 (&dst)[CPG][NV]) {
@@ -698,8 +774,8 @@ __global__ __launch_bounds__(1024) void s1_decode_kernel(S1Args a) {
       }
     };
     constexpr int STEP = 64 * CPG;
-    load_batch(0, kk[0]);
-    for (int c0 = 0; c0 < n_cand; c0 += 2 * STEP) {
+    if (!on_mfma) load_batch(0, kk[0]);
+    for (int c0 = 0; !on_mfma && c0 < n_cand; c0 += 2 * STEP) {
       if (c0 + STEP < n_cand) load_batch(c0 + STEP, kk[1]);
       use_batch(c0, kk[0]);
       if (c0 + STEP < n_cand) {
