@@ -89,6 +89,18 @@ def timed(fn, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps
 
 
+def timed_each(fn, steps, torch):
+    """Per-call ms of `steps` further calls (one event pair each): median, min, max."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for e0, e1 in ev:
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    t = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    return {"median": t[len(t) // 2], "min": t[0], "max": t[-1], "calls": steps}
+
+
 def popcount32(x, torch):
     x = x.to(torch.int64) & 0xFFFFFFFF
     x = x - ((x >> 1) & 0x55555555)
@@ -141,6 +153,7 @@ def bench_prefill(w, steps, warmup, torch, B, make_inputs, sensors=None):
     torch.cuda.synchronize()
     st = prefill_stats(w, lists, torch)
     t_all = timed(lambda: B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws), steps, warmup, torch)
+    t_all_each = timed_each(lambda: B.dash_attn_prefill(p, q, k, v, o, kbar, lists, ws), max(steps, 20), torch)
     t_s0 = timed(lambda: B.dash_kbar_compress(p, k, kbar), steps, 1, torch)
     # Stage 0 in its learned form (one summary query per kv-head), timed beside the block mean
     qbar = torch.randn((w.h_kv, w.head_dim), dtype=torch.float32, device=dev)
@@ -157,7 +170,7 @@ def bench_prefill(w, steps, warmup, torch, B, make_inputs, sensors=None):
         t_s2, sn_s2 = sensors.during(lambda: timed(lambda: B.dash_stage2_attend(p, q, k, v, o, lists, ws), steps, 1, torch))
         t_dense, sn_d = sensors.during(lambda: timed(lambda: B.dense_attn(p, q, k, v, od, ws), steps, warmup, torch))
         sens = {"stage2_loop": sn_s2, "dense_loop": sn_d}
-    res = dict(sensors=sens, ms_step=t_all, ms_stage0=t_s0, ms_stage0_learned=t_s0l, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
+    res = dict(sensors=sens, ms_step_each=t_all_each, ms_step=t_all, ms_stage0=t_s0, ms_stage0_learned=t_s0l, ms_stage1=t_s1, ms_stage2=t_s2, ms_dense=t_dense, **st)
     del q, k, v, o, od, ws, lists, kbar, kbar_l
     torch.cuda.empty_cache()
     return res
@@ -621,6 +634,8 @@ def main():
                                               (main_res["ms_stage0_learned"] * 1e-3) / 1e9,
                                "block_mean_k_read_GBps": w.batch * w.h_kv * w.n_kv * w.head_dim * 2 /
                                                          (main_res["ms_stage0"] * 1e-3) / 1e9},
+            # the same step timed call by call (20 calls after the timed loop): median / min / max in ms
+            "ms_step_per_call": main_res["ms_step_each"],
             "speedup_vs_dense": main_res["ms_dense"] / main_res["ms_step"],
             "stage2_speedup_vs_dense": main_res["ms_dense"] / main_res["ms_stage2"],
             "dense_tflops": tf(main_res["f_dense"], main_res["ms_dense"]),
