@@ -593,6 +593,18 @@ def main():
     w75 = w.replace(gamma=1.5)
     res75 = bench_prefill(w75, a.steps, a.warmup, torch, B, make_inputs)
     sweep = None if a.no_sweep else c4_sweep(torch, B, make_inputs, C4, a.small)
+    # the same configuration with queries that vary smoothly along the sequence (AR(1) over tokens, not a
+    # configuration of the paper): neighbouring tokens then keep similar chunks and an MFMA tile's union shrinks
+    corr = None
+    if not (a.no_sweep or a.small):
+        corr = {}
+        for rho in (0.9, 0.97, 0.99):
+            r = bench_prefill(w.replace(gamma=1.5, query_corr=rho), max(a.steps // 2, 3), 2, torch, B, make_inputs)
+            corr[f"rho_{rho}"] = {"gamma": 1.5, "chunk_sparsity": r["sparsity"], "ms_step": r["ms_step"], "ms_stage2": r["ms_stage2"],
+                                  "ms_dense": r["ms_dense"], "speedup_vs_dense": r["ms_dense"] / r["ms_step"],
+                                  "stage2_speedup_vs_dense": r["ms_dense"] / r["ms_stage2"],
+                                  "f_alg_over_f_exec": r["f_alg"] / r["f_exec"],
+                                  "effective_tflops": r["f_dense"] / (r["ms_step"] * 1e-3) / 1e12}
     c1 = c1_time(torch, B, make_inputs, C1, a.steps)
     mb = None if a.small else microbench(torch, a.steps)
     # the paper's own benchmark shape (GQA group 16, randomised masks) at its 32K point; all four lengths: --paper-protocol
@@ -651,6 +663,7 @@ def main():
             "C1_fp32_single_head": c1,
             "C4_sweep_128k": sweep,
             "paper_protocol_32k": pp32,
+            "correlated_queries_32k": corr,
             # the oracle on the host cores for the other configurations: rows per second on a 3 s sample and
             # the whole configuration's time extrapolated from it (rows are independent)
             "oracle_on_host": None if orc_res is None else {

@@ -46,6 +46,7 @@ class Workload:
     offset_sigma: float = 0.5    # std of the per-block key offset
     needles: int = 0             # >0: needle recipe instead of offsets
     needle_gain: float = 2.0
+    query_corr: float = 0.0      # >0: queries of consecutive tokens follow an AR(1) process with this coefficient
     seed: int = 0
 
     def replace(self, **kw) -> "Workload":
@@ -102,6 +103,30 @@ def _add_block_structure(w: Workload, k: torch.Tensor, gen, device) -> None:
         k += off
 
 
+def _correlate_tokens(x: torch.Tensor, rho: float) -> None:
+    """In place, along the token axis of x [heads, tokens, d]: x_t <- rho x_{t-1} + sqrt(1 - rho^2) x_t
+    (x_0 unchanged), a stationary AR(1) process with unit variance per element.  Not part of any
+    configuration of the paper: its kernel benchmark draws independent masks, real queries of
+    neighbouring tokens are similar; bench.py reports this variant beside the independent one."""
+    n = x.shape[1]
+    blk = 256
+    i = torch.arange(blk, device=x.device, dtype=torch.float64)
+    low = torch.tril(rho ** (i.view(-1, 1) - i.view(1, -1)).clamp(min=0)).to(torch.float32)   # rho^(i-j), j <= i
+    carry_w = (rho ** (i + 1)).to(torch.float32).view(1, -1, 1)
+    s = (1.0 - rho * rho) ** 0.5
+    prev = None
+    for t0 in range(0, n, blk):
+        m = min(blk, n - t0)
+        e = x[:, t0:t0 + m] * s
+        if prev is None:
+            e[:, 0] = x[:, 0]          # the first token keeps unit variance
+        y = torch.matmul(low[:m, :m], e)
+        if prev is not None:
+            y += carry_w[:, :m] * prev.unsqueeze(1)
+        x[:, t0:t0 + m] = y
+        prev = y[:, -1].clone()
+
+
 def make_inputs(w: Workload, device="cpu") -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """Return (q, k, v) in the run dtype.
 
@@ -117,7 +142,11 @@ def make_inputs(w: Workload, device="cpu") -> Tuple[torch.Tensor, torch.Tensor, 
     k = torch.empty((w.batch, w.h_kv, w.n_kv, w.head_dim), dtype=dt, device=device)
     v = torch.empty_like(k)
     for b in range(w.batch):
-        q[b] = _randn((w.h_q, w.n_q, w.head_dim), gen, device).to(dt)
+        qb = _randn((w.h_q, w.n_q, w.head_dim), gen, device)
+        if w.query_corr > 0.0:
+            _correlate_tokens(qb, w.query_corr)
+        q[b] = qb.to(dt)
+        del qb
         kb = _randn((w.h_kv, w.n_kv, w.head_dim), gen, device)
         vb = _randn((w.h_kv, w.n_kv, w.head_dim), gen, device)
         _add_block_structure(w, kb, gen, device)

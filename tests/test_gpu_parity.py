@@ -566,6 +566,7 @@ def gen_dev(w):
     ("mid_gqa4_8k_sparse", 1, 8, 2, 8192, 128, 64, {"gamma": 1.5, "offset_sigma": 0.7}),
     ("mid_b128_16k", 1, 4, 1, 16384, 128, 128, {"alpha": 2.0}),
     ("mid_needles_gqa1", 2, 2, 2, 8192, 128, 64, {"needles": 4, "offset_sigma": 0.0}),
+    ("mid_gqa4_correlated_queries", 1, 8, 2, 8192, 128, 64, {"gamma": 1.5, "query_corr": 0.97}),
 ], ids=lambda c: c[0])
 def test_prefill_mid_sampled(case):
     name, batch, h_q, h_kv, n, d, block, extra = case
