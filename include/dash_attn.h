@@ -18,7 +18,8 @@
  *     variable, and enqueues all work on `stream` (a hipStream_t passed as void*;
  *     NULL = the default stream).  Nothing a call computes depends on an earlier
  *     call: the only thing the library remembers is, per device, that a kernel's
- *     one-time opt-in to more than 64 KB of LDS has been made (thread-safe).
+ *     one-time opt-in to a large dynamic LDS size has been made (thread-safe), and the
+ *     address of the scratch array of dash_attn_decode_static.
  *     Entry points may be called from several threads.
  *   - Tensors are [batch, head, token, head_dim] with head_dim contiguous; the
  *     other three strides are given in ELEMENTS in dash_params.  Rows must be
@@ -39,6 +40,11 @@
  *     chunk is a candidate, there is no diagonal branch, and n_kv must be a
  *     multiple of block_size (dense_attn and the size queries accept any n_kv).
  *   - kbar pointers may be NULL when n_kv < block_size (no complete chunk).
+ *   - Limits of this build (DASH_EUNSUPPORTED beyond them): at most 2048 chunks per
+ *     sequence, ceil(n_kv / block_size) <= 2048 (131072 tokens at chunks of 64, 262144 at
+ *     128); a call with several queries (n_q > 1) that continues a longer cache must start
+ *     at a multiple of 64 tokens, (n_kv - n_q) % 64 == 0; head_dim 64 or 128; block_size
+ *     64 or 128; h_q / h_kv in {1, 2, 4, 8, 16}; window <= 8.
  */
 #ifndef DASH_ATTN_H_
 #define DASH_ATTN_H_
