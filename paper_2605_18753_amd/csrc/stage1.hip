@@ -1002,13 +1002,13 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
   // Token ranges, each launched with the kernel and the sizes that fit its longest row
   // (causal rows grow with the position; boundaries at multiples of 64 tokens, longest
   // range first).  The register-resident kernels take the tokens whose rows have up to
-  // 512 candidates, and those with up to 1536 (head dimension 128), as one range each.
+  // 256, up to 512, and up to 1536 candidates (the last at head dimension 128), one range each.
   // What is left goes to the kernel below, which keeps the score rows of a workgroup in
   // LDS, sized for the longest row of its launch: there a long prefill is cut into four
   // ranges, so that the early ones get more rows per workgroup (fewer re-reads of the
   // summaries) and more workgroups per CU.  Measured with that kernel alone: 96k tokens,
   // GQA group 16: 25.9 -> 17.9 ms; 128k tokens, chunk 128: 12.5 -> 11.0 ms.
-  int bounds[8];
+  int bounds[9];
   int nb = 0;
   bounds[nb++] = 0;
   if (p.causal && p.n_q > 1 && !L.seq_lens) {
@@ -1019,9 +1019,11 @@ hipError_t launch_s1_route(const dash_params& p, const Layout& L, const void* q,
     };
     int lds_from = 0;   // tokens from here on go to the LDS-row kernel
     if (mfma) {
+      const int t256 = first_beyond(256);
+      if (t256 > 0 && t256 < p.n_q) bounds[nb++] = t256;
       const int t512 = first_beyond(512);
       const int t1536 = p.head_dim == 128 ? first_beyond(1536) : t512;
-      if (t512 > 0 && t512 < p.n_q) bounds[nb++] = t512;
+      if (t512 > t256 && t512 < p.n_q) bounds[nb++] = t512;
       if (t1536 > t512 && t1536 < p.n_q) bounds[nb++] = t1536;
       lds_from = t1536;
     }

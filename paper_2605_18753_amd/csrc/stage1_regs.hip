@@ -15,9 +15,11 @@
 // tokens (g_q <= 4) or a quarter or half of one token's heads (g_q = 16, 8: the group
 // weight is then completed across DPP rows).  A wave owns 16 rows and walks all chunk
 // tiles; the waves of a workgroup share every tile of split summaries through LDS
-// (buffer_load ... lds, a ring of five stages), so a tile is fetched once per workgroup:
-//   rows of up to 512 chunks:  8 waves x 16 rows = 128 rows, at most 128 score registers
-//                              per lane;
+// (buffer_load ... lds, a ring of three or five stages), so a tile is fetched once per workgroup:
+//   rows of up to 256 chunks:  8 waves x 16 rows = 128 rows, at most 64 score registers
+//                              per lane: two workgroups per CU (four waves per SIMD);
+//   rows of up to 512 chunks:  the same with up to 128 score registers, one workgroup
+//                              per CU;
 //   rows of up to 1536 chunks: the 8 waves form 4 pairs (64 rows); the waves of a pair
 //                              hold the first and the second half of the same 16 rows
 //                              (up to 192 score registers per lane) and combine their
@@ -48,7 +50,7 @@ namespace dash {
 #error "compile with -DDASH_S1R_G=<GQA group size: 1, 2, 4, 8 or 16>"
 #endif
 
-template <int D> struct RegsCfg {
+template <int D, int STAGES_> struct RegsCfg {
   static constexpr int NW = 8;                               // waves per workgroup
   static constexpr int KS = D / 32;                          // contraction steps per product
   static constexpr int PART_BYTES = D * 2;                   // one bf16 piece of a summary
@@ -58,7 +60,7 @@ template <int D> struct RegsCfg {
   static constexpr int TILE_BYTES = 16 * ROW_BYTES;          // 16 chunks
   static constexpr int IPW = (TILE_BYTES / 1024 + NW - 1) / NW;   // copy instructions per wave and tile
   static constexpr int STAGE_BYTES = IPW * NW * 1024;        // tile + room for the surplus instructions' zeros
-  static constexpr int STAGES = 5;                           // one workgroup per CU: LDS is there to be used
+  static constexpr int STAGES = STAGES_;                     // ring depth: 3 where two workgroups share a CU, 5 where one has it
   static_assert(STAGES >= 2 && STAGES <= 5, "the counted waits below cover up to three newer tiles in flight");
   static constexpr int RING_BYTES = STAGES * STAGE_BYTES;
   static constexpr int XCH_FLOATS = 2 * NW * 4 * 12;         // exchange area of the wave pairs (see PairX)
@@ -223,9 +225,9 @@ __device__ __forceinline__ void solve4(const f32x4 (&v)[NT], int n_cand, float a
 // One workgroup's rows with NT chunk tiles of 16 per wave.  SPLIT = 1: every wave holds
 // whole rows (n_cand <= 16 NT).  SPLIT = 2: waves w and w + 4 hold chunk tiles
 // [0, NT) and [NT, 2 NT) of the same 16 rows (n_cand <= 32 NT).
-template <int D, int G, int MODE, int SPLIT, int NT>
+template <int D, int G, int MODE, int SPLIT, int NT, int STAGES>
 __device__ __forceinline__ void regs_tile(const S1Args& a, char* lds, int b, int r, int tok0, int ntile) {
-  using C = RegsCfg<D>;
+  using C = RegsCfg<D, STAGES>;
   constexpr int TPL = G >= 4 ? 1 : 4 / G;     // tokens per lane (its four rows are TPL tokens x HPL heads)
   constexpr int HPL = G >= 4 ? 4 : G;         // heads of one token held by a lane
   constexpr int KQT = G > 4 ? G / 4 : 1;      // DPP rows that share one token (g_q = 8: 2, g_q = 16: 4)
@@ -446,10 +448,20 @@ __device__ __forceinline__ int regs_ntile(const S1Args& a, int tok0, int tokt) {
   return (n_max + 15) >> 4;
 }
 
-// SPLIT = 1: rows of up to 512 chunks, 128 rows per workgroup; SPLIT = 2: up to 1536, 64 rows
-template <int D, int G, int MODE, int SPLIT>
-__global__ __launch_bounds__(512) void s1_regs_kernel(S1Args a) {
+// The three kernels.  VAR 0: rows of up to 256 chunks, whole rows per wave, at most 64 score
+// registers per lane, so two workgroups (four waves per SIMD) share a CU, three-stage ring.
+// VAR 1: rows of up to 512 chunks, whole rows per wave, one workgroup per CU, five-stage ring.
+// VAR 2: rows of up to 1536 chunks split over wave pairs, 64 rows per workgroup.
+template <int VAR> struct RegsVar {
+  static constexpr int SPLIT = VAR == 2 ? 2 : 1;
+  static constexpr int STAGES = VAR == 0 ? 3 : 5;
+  static constexpr int MIN_WG = VAR == 0 ? 2 : 1;   // workgroups per CU the register budget is set for
+};
+
+template <int D, int G, int MODE, int VAR>
+__global__ __launch_bounds__(512, RegsVar<VAR>::MIN_WG) void s1_regs_kernel(S1Args a) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr int SPLIT = RegsVar<VAR>::SPLIT, ST = RegsVar<VAR>::STAGES;
   constexpr int TOKT = (8 / SPLIT) * 16 / G;   // tokens per workgroup
   const int hb = a.h_kv * a.batch;
   const int hbi = blockIdx.x % hb;
@@ -457,14 +469,15 @@ __global__ __launch_bounds__(512) void s1_regs_kernel(S1Args a) {
   const int r = hbi % a.h_kv, b = hbi / a.h_kv;
   const int tok0 = a.tok_base + tile * TOKT;
   const int ntile = regs_ntile(a, tok0, TOKT);
-  if constexpr (SPLIT == 1) {
-    if (ntile <= 4) regs_tile<D, G, MODE, 1, 4>(a, lds, b, r, tok0, ntile);
-    else if (ntile <= 8) regs_tile<D, G, MODE, 1, 8>(a, lds, b, r, tok0, ntile);
-    else if (ntile <= 16) regs_tile<D, G, MODE, 1, 16>(a, lds, b, r, tok0, ntile);
-    else regs_tile<D, G, MODE, 1, 32>(a, lds, b, r, tok0, ntile);
+  if constexpr (VAR == 0) {
+    if (ntile <= 4) regs_tile<D, G, MODE, 1, 4, ST>(a, lds, b, r, tok0, ntile);
+    else if (ntile <= 8) regs_tile<D, G, MODE, 1, 8, ST>(a, lds, b, r, tok0, ntile);
+    else regs_tile<D, G, MODE, 1, 16, ST>(a, lds, b, r, tok0, ntile);
+  } else if constexpr (VAR == 1) {
+    regs_tile<D, G, MODE, 1, 32, ST>(a, lds, b, r, tok0, ntile);
   } else {
-    if (ntile <= 64) regs_tile<D, G, MODE, 2, 32>(a, lds, b, r, tok0, ntile);
-    else regs_tile<D, G, MODE, 2, 48>(a, lds, b, r, tok0, ntile);
+    if (ntile <= 64) regs_tile<D, G, MODE, 2, 32, ST>(a, lds, b, r, tok0, ntile);
+    else regs_tile<D, G, MODE, 2, 48, ST>(a, lds, b, r, tok0, ntile);
   }
 }
 
@@ -476,17 +489,17 @@ static hipError_t launch_regs_k(const S1Args& a, dim3 grid, size_t lds, hipStrea
   return hipGetLastError();
 }
 
-template <int D, int G, int SPLIT>
+template <int D, int G, int VAR>
 static hipError_t launch_regs(const S1Args& a, int mode, hipStream_t st) {
-  constexpr size_t lds = RegsCfg<D>::LDS_BYTES;
-  constexpr int tokt = (8 / SPLIT) * 16 / G;
+  constexpr size_t lds = RegsCfg<D, RegsVar<VAR>::STAGES>::LDS_BYTES;
+  constexpr int tokt = (8 / RegsVar<VAR>::SPLIT) * 16 / G;
   const dim3 grid((unsigned)(((a.tok_end - a.tok_base + tokt - 1) / tokt) * a.h_kv * a.batch), 1, 1);
   switch (mode) {
-    case MODE_P1: return launch_regs_k<s1_regs_kernel<D, G, MODE_P1, SPLIT>>(a, grid, lds, st);
-    case MODE_P2: return launch_regs_k<s1_regs_kernel<D, G, MODE_P2, SPLIT>>(a, grid, lds, st);
-    case MODE_P4: return launch_regs_k<s1_regs_kernel<D, G, MODE_P4, SPLIT>>(a, grid, lds, st);
-    case MODE_GEN: return launch_regs_k<s1_regs_kernel<D, G, MODE_GEN, SPLIT>>(a, grid, lds, st);
-    default: return launch_regs_k<s1_regs_kernel<D, G, MODE_BISECT, SPLIT>>(a, grid, lds, st);
+    case MODE_P1: return launch_regs_k<s1_regs_kernel<D, G, MODE_P1, VAR>>(a, grid, lds, st);
+    case MODE_P2: return launch_regs_k<s1_regs_kernel<D, G, MODE_P2, VAR>>(a, grid, lds, st);
+    case MODE_P4: return launch_regs_k<s1_regs_kernel<D, G, MODE_P4, VAR>>(a, grid, lds, st);
+    case MODE_GEN: return launch_regs_k<s1_regs_kernel<D, G, MODE_GEN, VAR>>(a, grid, lds, st);
+    default: return launch_regs_k<s1_regs_kernel<D, G, MODE_BISECT, VAR>>(a, grid, lds, st);
   }
 }
 
@@ -497,6 +510,8 @@ static hipError_t launch_regs(const S1Args& a, int mode, hipStream_t st) {
 // has max_cand <= 512 candidates, or max_cand <= 1536 with head_dim 128.
 hipError_t DASH_CAT(launch_s1_regs_g, DASH_S1R_G)(const S1Args& a, int head_dim, int mode, int max_cand, hipStream_t st) {
   constexpr int G = DASH_S1R_G;
+  if (max_cand <= 256)
+    return head_dim == 128 ? launch_regs<128, G, 0>(a, mode, st) : launch_regs<64, G, 0>(a, mode, st);
   if (max_cand <= 512)
     return head_dim == 128 ? launch_regs<128, G, 1>(a, mode, st) : launch_regs<64, G, 1>(a, mode, st);
   return launch_regs<128, G, 2>(a, mode, st);
